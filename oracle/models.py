@@ -1,0 +1,185 @@
+"""CPU oracle: forward passes of the four served architectures in fp64.
+
+TEST INFRASTRUCTURE ONLY (see ops.py).  Written from the public definitions of the
+architectures; the paper fixes the workload only as "a sequence of dependent kernels"
+(Section 3.2) and lists ResNet-50 at 4.09 G multiply-accumulates (Table 1), which
+`Trace.total_macs` reproduces for the topology below.
+
+Every forward takes the seeded tensors (fp16 values) as a dict and returns a `Result` with the
+pre-softmax logits, probabilities and top-1 indices, plus a `Trace` of per-layer multiply-
+accumulate counts and (optionally) every layer's input and output for per-kernel checks.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from . import ops
+
+ARCH_TINY_CNN, ARCH_RESNET50, ARCH_MOBILENETV2, ARCH_ENCODER = 0, 1, 2, 3
+FP16_MAX = 65504.0
+
+
+@dataclass
+class Layer:
+    name: str
+    kind: str
+    macs: int
+    out_shape: tuple
+    max_abs: float
+
+
+@dataclass
+class Trace:
+    layers: List[Layer] = field(default_factory=list)
+    keep: bool = False
+    acts: Dict[str, np.ndarray] = field(default_factory=dict)
+
+    def add(self, name, kind, macs, y):
+        self.layers.append(Layer(name, kind, int(macs), tuple(y.shape), float(np.abs(y).max())))
+        if self.keep:
+            self.acts[name] = y
+
+    @property
+    def total_macs(self) -> int:
+        return sum(l.macs for l in self.layers)
+
+    def n_kind(self, kind) -> int:
+        return sum(1 for l in self.layers if l.kind == kind)
+
+
+@dataclass
+class Result:
+    logits: np.ndarray            # CNN: [N, classes]; encoder: hidden states [B, S, hidden]
+    probs: Optional[np.ndarray]
+    top1: np.ndarray              # int32
+    trace: Trace
+
+
+def _conv_unit(t, tr, name, x, stride, pad, act, bn=True, depthwise=False):
+    w = t[name + ".w"]
+    if bn:
+        w, b = ops.fold_bn(w, t[name + ".gamma"], t[name + ".beta"], t[name + ".mean"], t[name + ".var"])
+    else:
+        b = t[name + ".b"].astype(np.float32)
+    if depthwise:
+        y = ops.dwconv2d(x, w, b, stride, pad)
+        macs = y.size * w.shape[2] * w.shape[3]
+    else:
+        y = ops.conv2d(x, w, b, stride, pad)
+        macs = y.size * w.shape[1] * w.shape[2] * w.shape[3]
+    if act == "relu":
+        y = ops.relu(y)
+    elif act == "relu6":
+        y = ops.relu6(y)
+    tr.add(name, "dwconv" if depthwise else "conv", macs, y)
+    return y
+
+
+def _head(t, tr, feat):
+    logits = ops.linear(feat, t["fc.w"], t["fc.b"])
+    tr.add("fc", "fc", logits.size * feat.shape[-1], logits)
+    return Result(logits, ops.softmax(logits), ops.argmax_first(logits), tr)
+
+
+def tiny_cnn_forward(t, x, keep=False) -> Result:
+    """conv3x3(16,s1,p1)+ReLU -> conv3x3(32,s2,p1)+ReLU -> conv3x3(64,s2,p1)+ReLU -> GAP -> FC -> softmax."""
+    tr = Trace(keep=keep)
+    y = np.asarray(x, np.float64)
+    for i, stride in enumerate((1, 2, 2)):
+        y = _conv_unit(t, tr, f"conv{i}", y, stride, 1, "relu", bn=False)
+    feat = ops.global_avg_pool(y)
+    tr.add("gap", "pool", 0, feat)
+    return _head(t, tr, feat)
+
+
+def resnet50_forward(t, x, keep=False) -> Result:
+    """ResNet-50 v1.5: the stride of a down-sampling bottleneck sits on its 3x3 convolution."""
+    tr = Trace(keep=keep)
+    y = _conv_unit(t, tr, "stem", np.asarray(x, np.float64), 2, 3, "relu")
+    y = ops.maxpool2d(y, 3, 2, 1)
+    tr.add("maxpool", "pool", 0, y)
+    for si, nb in enumerate((3, 4, 6, 3), start=1):
+        for bi in range(nb):
+            p = f"s{si}b{bi}"
+            stride = 2 if (bi == 0 and si > 1) else 1
+            a = _conv_unit(t, tr, p + ".c1", y, 1, 0, "relu")
+            a = _conv_unit(t, tr, p + ".c2", a, stride, 1, "relu")
+            a = _conv_unit(t, tr, p + ".c3", a, 1, 0, None)
+            sc = _conv_unit(t, tr, p + ".down", y, stride, 0, None) if bi == 0 else y
+            y = ops.relu(a + sc)
+            tr.add(p + ".out", "add", 0, y)
+    feat = ops.global_avg_pool(y)
+    tr.add("gap", "pool", 0, feat)
+    return _head(t, tr, feat)
+
+
+MOBILENETV2_CFG = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
+                   (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
+
+
+def mobilenet_v2_forward(t, x, keep=False) -> Result:
+    """MobileNetV2 1.0: inverted residuals, ReLU6, linear bottlenecks; a block has a residual
+    connection iff its stride is 1 and its input and output widths agree."""
+    tr = Trace(keep=keep)
+    y = _conv_unit(t, tr, "stem", np.asarray(x, np.float64), 2, 1, "relu6")
+    cin, idx = 32, 0
+    for tt, c, n, s in MOBILENETV2_CFG:
+        for i in range(n):
+            stride = s if i == 0 else 1
+            p = f"b{idx}"
+            a = y
+            if tt != 1:
+                a = _conv_unit(t, tr, p + ".expand", a, 1, 0, "relu6")
+            a = _conv_unit(t, tr, p + ".dw", a, stride, 1, "relu6", depthwise=True)
+            a = _conv_unit(t, tr, p + ".project", a, 1, 0, None)
+            if stride == 1 and cin == c:
+                a = a + y
+                tr.add(p + ".out", "add", 0, a)
+            y, cin, idx = a, c, idx + 1
+    y = _conv_unit(t, tr, "head", y, 1, 0, "relu6")
+    feat = ops.global_avg_pool(y)
+    tr.add("gap", "pool", 0, feat)
+    return _head(t, tr, feat)
+
+
+def encoder_forward(t, x, valid_len, hyper, keep=False) -> Result:
+    """Post-LayerNorm Transformer encoder stack:
+         h = LN(x + Attn(x) W_o + b_o);  y = LN(h + GELU(h W_1 + b_1) W_2 + b_2)."""
+    layers, hidden, heads, ffn, seq = hyper
+    tr = Trace(keep=keep)
+    y = np.asarray(x, np.float64)
+    bsz = y.shape[0]
+    ntok = bsz * seq
+    attn_macs = int(sum(2 * seq * int(L) * hidden for L in valid_len))
+    for i in range(layers):
+        p = f"l{i}"
+        q = ops.linear(y, t[p + ".q.w"], t[p + ".q.b"])
+        k = ops.linear(y, t[p + ".k.w"], t[p + ".k.b"])
+        v = ops.linear(y, t[p + ".v.w"], t[p + ".v.b"])
+        tr.add(p + ".qkv", "gemm", 3 * ntok * hidden * hidden, np.concatenate([q, k, v], axis=-1))
+        a = ops.attention(q, k, v, valid_len, heads)
+        tr.add(p + ".attn", "attention", attn_macs, a)
+        o = ops.linear(a, t[p + ".o.w"], t[p + ".o.b"])
+        h = ops.layernorm(y + o, t[p + ".ln1.g"], t[p + ".ln1.b"])
+        tr.add(p + ".ln1", "gemm", ntok * hidden * hidden, h)
+        f = ops.gelu(ops.linear(h, t[p + ".ffn1.w"], t[p + ".ffn1.b"]))
+        tr.add(p + ".ffn1", "gemm", ntok * hidden * ffn, f)
+        f = ops.linear(f, t[p + ".ffn2.w"], t[p + ".ffn2.b"])
+        y = ops.layernorm(h + f, t[p + ".ln2.g"], t[p + ".ln2.b"])
+        tr.add(p + ".ln2", "gemm", ntok * hidden * ffn, y)
+    return Result(y, None, ops.argmax_first(y[:, 0, :]), tr)
+
+
+def forward(arch, tensors, x, valid_len=None, hyper=None, keep=False) -> Result:
+    if arch == ARCH_TINY_CNN:
+        return tiny_cnn_forward(tensors, x, keep)
+    if arch == ARCH_RESNET50:
+        return resnet50_forward(tensors, x, keep)
+    if arch == ARCH_MOBILENETV2:
+        return mobilenet_v2_forward(tensors, x, keep)
+    if arch == ARCH_ENCODER:
+        return encoder_forward(tensors, x, valid_len, hyper, keep)
+    raise ValueError(arch)
