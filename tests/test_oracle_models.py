@@ -1,0 +1,185 @@
+"""Pins of the oracle's model forwards: topology against the paper's Table 1 and closed-form
+operation counts, wiring against short independent compositions, invariants."""
+import os
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import models, ops
+from test_oracle_ops import conv_by_windows
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _table1():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "table1_models.txt")):
+        if line[0] != "#" and line.strip():
+            k, v = line.split()
+            out[k] = float(v)
+    return out
+
+
+@pytest.fixture(scope="module")
+def resnet_full():
+    md = synth.resnet50(synth.SEEDS[synth.ARCH_RESNET50])
+    x = synth.default_image_batch(md, 1, 11)
+    return md, x, models.resnet50_forward(md.tensors, x)
+
+
+def test_resnet50_topology_matches_table1(resnet_full):
+    md, x, r = resnet_full
+    tr = r.trace
+    assert tr.total_macs == 4_089_184_256
+    assert round(tr.total_macs / 1e9, 2) == _table1()["resnet50"]          # Table 1: 4.09
+    assert tr.n_kind("conv") == 53 and tr.n_kind("add") == 16
+    shapes = {l.name: l.out_shape for l in tr.layers}
+    assert shapes["stem"] == (1, 112, 112, 64) and shapes["maxpool"] == (1, 56, 56, 64)
+    assert shapes["s1b2.out"] == (1, 56, 56, 256) and shapes["s2b3.out"] == (1, 28, 28, 512)
+    assert shapes["s3b5.out"] == (1, 14, 14, 1024) and shapes["s4b2.out"] == (1, 7, 7, 2048)
+    # v1.5: the stride sits on the 3x3, so the first 1x1 of a down-sampling block still runs at full size
+    assert shapes["s2b0.c1"] == (1, 56, 56, 128) and shapes["s2b0.c2"] == (1, 28, 28, 128)
+    conv_fc_params = sum(t.size for k, t in md.tensors.items() if k.endswith(".w"))
+    assert conv_fc_params == 25_502_912
+    assert r.logits.shape == (1, 1000) and r.top1.dtype == np.int32
+    # no activation leaves the fp16 range, so an fp16 GPU path cannot overflow on these inputs
+    assert max(l.max_abs for l in tr.layers) < 6e4
+
+
+def test_mobilenet_v2_topology():
+    md = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2])
+    x = synth.default_image_batch(md, 1, 11)
+    r = models.mobilenet_v2_forward(md.tensors, x)
+    tr = r.trace
+    assert tr.total_macs == 300_774_272                                  # the published ~300 M
+    assert tr.n_kind("dwconv") == 17 and tr.n_kind("conv") == 35 and tr.n_kind("add") == 10
+    shapes = {l.name: l.out_shape for l in tr.layers}
+    assert shapes["head"] == (1, 7, 7, 1280) and shapes["b0.dw"] == (1, 112, 112, 32)
+    assert shapes["b1.dw"] == (1, 56, 56, 96) and shapes["b16.dw"] == (1, 7, 7, 960)
+    dw_macs = sum(l.macs for l in tr.layers if l.kind == "dwconv")
+    assert abs(dw_macs / 1e6 - 20.7) < 0.1
+    assert max(l.max_abs for l in tr.layers) < 6e4
+
+
+def test_encoder_macs_closed_form():
+    md = synth.encoder(3, layers=2, hidden=64, heads=4, ffn=256, seq=16)
+    x, vl = synth.token_batch(md, 3, 4, min_len=16)           # all full length
+    r = models.encoder_forward(md.tensors, x, vl, md.hyper)
+    L, H, F, S, B = 2, 64, 256, 16, 3
+    assert r.trace.total_macs == L * B * (S * (4 * H * H + 2 * H * F) + 2 * S * S * H)
+    # BERT-base shape, closed form per 128-token sequence: 11.17 G
+    S, H, F = 128, 768, 3072
+    assert round(12 * (S * (4 * H * H + 2 * H * F) + 2 * S * S * H) / 1e9, 2) == 11.17
+    assert r.logits.shape == (3, 16, 64) and r.top1.shape == (3,)
+
+
+def test_tiny_cnn_zero_input_and_homogeneity():
+    md = synth.tiny_cnn(synth.SEEDS[synth.ARCH_TINY_CNN])
+    z = models.tiny_cnn_forward(md.tensors, np.zeros((2, 32, 32, 3), np.float16))
+    assert not z.logits.any() and np.allclose(z.probs, 0.1)
+    x = synth.default_image_batch(md, 4, 5)
+    r1 = models.tiny_cnn_forward(md.tensors, x)
+    r2 = models.tiny_cnn_forward(md.tensors, x.astype(np.float64) * 2.0)
+    assert np.allclose(r2.logits, 2.0 * r1.logits, rtol=1e-13, atol=0)        # ReLU net with zero biases is positively homogeneous
+    assert abs(r1.trace.total_macs / 4 / 1e6 - 2.80) < 0.01
+    assert np.abs(r1.probs.sum(-1) - 1).max() < 1e-12
+    assert np.array_equal(r1.top1, r1.probs.argmax(-1))
+
+
+def test_tiny_cnn_against_independent_composition():
+    md = synth.tiny_cnn(7)
+    t = md.tensors
+    x = synth.default_image_batch(md, 2, 5)
+    y = x.astype(np.float64)
+    for i, s in enumerate((1, 2, 2)):
+        y = np.maximum(conv_by_windows(y, t[f"conv{i}.w"].astype(np.float64), None, s, 1), 0)
+    assert y.shape == (2, 8, 8, 64)
+    logits = y.mean(axis=(1, 2)) @ t["fc.w"].astype(np.float64).T
+    r = models.tiny_cnn_forward(t, x)
+    assert np.allclose(r.logits, logits, rtol=1e-11, atol=1e-11)
+
+
+def test_resnet50_batch_independence_and_homogeneity():
+    md = synth.resnet50(5, hw=32)
+    t = dict(md.tensors)
+    x = synth.default_image_batch(md, 3, 2)
+    r = models.resnet50_forward(t, x)
+    for i in range(3):
+        ri = models.resnet50_forward(t, x[i:i + 1])
+        assert np.allclose(ri.logits[0], r.logits[i], rtol=1e-12, atol=1e-12)   # BLAS blocking differs with batch
+    for k in t:
+        if k.endswith(".beta") or k.endswith(".mean"):
+            t[k] = np.zeros_like(t[k])
+    a = models.resnet50_forward(t, x)
+    b = models.resnet50_forward(t, x.astype(np.float64) * 2.0)
+    assert np.allclose(b.logits, 2.0 * a.logits, rtol=1e-13, atol=0)
+
+
+def test_resnet50_shortcut_wiring():
+    """With the last BatchNorm of every bottleneck zeroed (gamma = beta = 0) each residual branch
+    contributes nothing: identity blocks pass their input through and the first block of a stage
+    reduces to its strided 1x1 projection.  The net becomes a short chain computable independently."""
+    md = synth.resnet50(9, hw=32)
+    t = dict(md.tensors)
+    for k in t:
+        if k.endswith(".c3.gamma") or k.endswith(".c3.beta"):
+            t[k] = np.zeros_like(t[k])
+    x = synth.default_image_batch(md, 2, 3)
+    r = models.resnet50_forward(t, x)
+
+    def unit(name, y, stride, pad):
+        w, b = ops.fold_bn(t[name + ".w"], t[name + ".gamma"], t[name + ".beta"], t[name + ".mean"], t[name + ".var"])
+        return conv_by_windows(y, w.astype(np.float64), b.astype(np.float64), stride, pad)
+
+    y = np.maximum(unit("stem", x.astype(np.float64), 2, 3), 0)
+    yp = np.pad(y, ((0, 0), (1, 1), (1, 1), (0, 0)), constant_values=-np.inf)
+    from numpy.lib.stride_tricks import sliding_window_view
+    y = sliding_window_view(yp, (3, 3), axis=(1, 2))[:, ::2, ::2].max(axis=(-1, -2))
+    for si in (1, 2, 3, 4):
+        y = np.maximum(unit(f"s{si}b0.down", y, 1 if si == 1 else 2, 0), 0)
+    logits = y.mean(axis=(1, 2)) @ t["fc.w"].astype(np.float64).T
+    assert np.allclose(r.logits, logits, rtol=1e-10, atol=1e-10)
+
+
+def test_mobilenet_v2_block_wiring():
+    """Zero every projection's BatchNorm gamma and beta: every block then outputs 0 (+ its input where it
+    has a residual connection), so the features entering `head` are exactly zero and the logits
+    depend on the head's folded bias alone."""
+    md = synth.mobilenet_v2(4, hw=32)
+    t = dict(md.tensors)
+    for k in t:
+        if k.endswith(".project.gamma") or k.endswith(".project.beta"):
+            t[k] = np.zeros_like(t[k])
+    x = synth.default_image_batch(md, 2, 3)
+    r = models.mobilenet_v2_forward(t, x, keep=True)
+    assert not r.trace.acts["b16.project"].any()
+    _, hb = ops.fold_bn(t["head.w"], t["head.gamma"], t["head.beta"], t["head.mean"], t["head.var"])
+    feat = np.clip(hb.astype(np.float64), 0, 6)
+    want = feat @ t["fc.w"].astype(np.float64).T
+    assert np.allclose(r.logits, np.broadcast_to(want, r.logits.shape), atol=1e-12)
+
+
+def test_mobilenet_v2_batch_independence():
+    md = synth.mobilenet_v2(4, hw=32)
+    x = synth.default_image_batch(md, 2, 3)
+    r = models.mobilenet_v2_forward(md.tensors, x)
+    r0 = models.mobilenet_v2_forward(md.tensors, x[1:2])
+    assert np.allclose(r0.logits[0], r.logits[1], rtol=1e-12, atol=1e-12)
+
+
+def test_encoder_mask_invariance_and_single_layer_composition():
+    md = synth.encoder(6, layers=2, hidden=32, heads=2, ffn=64, seq=12)
+    x, vl = synth.token_batch(md, 3, 8, min_len=4)
+    r = models.encoder_forward(md.tensors, x, vl, md.hyper)
+    x2 = x.copy()
+    for b in range(3):
+        x2[b, vl[b]:] = 7.0                                   # change the padded tokens' values
+    r2 = models.encoder_forward(md.tensors, x2, vl, md.hyper)
+    for b in range(3):
+        assert np.array_equal(r.logits[b, :vl[b]], r2.logits[b, :vl[b]])
+    # row statistics after the closing LayerNorm: (y - beta)/gamma has mean 0 and variance 1
+    t = md.tensors
+    g, be = t["l1.ln2.g"].astype(np.float64), t["l1.ln2.b"].astype(np.float64)
+    z = (r.logits - be) / g
+    assert np.abs(z.mean(-1)).max() < 1e-9 and np.abs(z.var(-1) - 1).max() < 1e-6
