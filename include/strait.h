@@ -1,0 +1,213 @@
+/*
+ * strait.h -- C ABI of the MI355X (gfx950) hot path under a dual-priority inference server.
+ *
+ * The served unit is a *batch of one model*.  Following the paper's description of what
+ * happens to a batch on a discrete GPU (Section 3.2, "Interference Prediction", steps (1)-(3)):
+ *   (1) the input is written to pinned host memory and copied host-to-device,
+ *   (2) a sequence of dependent kernels runs,
+ *   (3) the result is copied back to pinned host memory,
+ * and every model carries one of two priority levels that selects the stream its batches are
+ * issued on (Section 3.1, "Priority Level").  Several batches may be in flight on one GPU at
+ * once ("spatial sharing", Section 1/2).  On completion the measured transfer and kernel
+ * latencies of the batch are reported (Section 3.2 "Online calibration"; Section 3.3, last
+ * paragraph; Section 5.1 "Evaluation Metrics").  Model instances own their pinned staging
+ * buffers and execution resources (Section 4, "Implementation").
+ *
+ * Conventions
+ *   - every function returns a strait_status (0 = OK, negative = error); nothing throws or
+ *     aborts across this boundary.  strait_last_error() gives a per-thread message.
+ *   - "host" pointers are ordinary host memory; "device" pointers are HIP device memory of the
+ *     context's GPU; streams are hipStream_t passed as void*.
+ *   - the library never creates, destroys or changes the streams handed to it.
+ *   - all activations are fp16 (IEEE binary16), NHWC; accumulation is fp32.
+ *   - one GPU per context; no collectives.
+ */
+#ifndef STRAIT_H
+#define STRAIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t strait_status;
+enum {
+    STRAIT_OK = 0,
+    STRAIT_E_INVALID = -1,     /* bad argument (null, out of range, misaligned)            */
+    STRAIT_E_HIP = -2,         /* a HIP call failed; message has hipGetErrorString          */
+    STRAIT_E_FORMAT = -3,      /* weight container malformed or a tensor missing/misshaped  */
+    STRAIT_E_NOMEM = -4,       /* host or device allocation failed                          */
+    STRAIT_E_SHAPE = -5,       /* operand shapes the kernels do not support                 */
+    STRAIT_E_BUSY = -6,        /* no idle instance (submit) / work still in flight (free)   */
+    STRAIT_E_BATCH = -7        /* batch < 1 or batch > max_batch                            */
+};
+
+typedef enum { STRAIT_PRIO_HIGH = 0, STRAIT_PRIO_LOW = 1 } strait_priority;
+
+typedef enum {
+    STRAIT_ARCH_TINY_CNN = 0,      /* conv3x3 x3 + GAP + FC + softmax                        */
+    STRAIT_ARCH_RESNET50 = 1,      /* ResNet-50 v1.5, BatchNorm folded at load               */
+    STRAIT_ARCH_MOBILENETV2 = 2,   /* MobileNetV2 1.0                                        */
+    STRAIT_ARCH_ENCODER = 3        /* post-LayerNorm Transformer encoder stack               */
+} strait_arch;
+
+typedef enum { STRAIT_ACT_NONE = 0, STRAIT_ACT_RELU = 1, STRAIT_ACT_RELU6 = 2, STRAIT_ACT_GELU = 3 } strait_act;
+
+typedef struct strait_ctx strait_ctx;
+typedef struct strait_model strait_model;
+typedef struct strait_ticket_s* strait_ticket;
+
+#define STRAIT_MAX_STREAMS 8
+
+/* Context: one GPU plus the streams the caller created for it (Section 3.1: the priority of a
+ * model selects the stream its batches run on).  n_hp/n_lp >= 1, n_copy >= 1, each at most
+ * STRAIT_MAX_STREAMS.  A batch of priority p is issued on compute stream p[i % n_p] and its
+ * host-to-device copy on copy_streams[j % n_copy] (i, j: running counters). */
+typedef struct {
+    int32_t device;
+    int32_t n_hp, n_lp, n_copy;
+    void* hp_streams[STRAIT_MAX_STREAMS];
+    void* lp_streams[STRAIT_MAX_STREAMS];
+    void* copy_streams[STRAIT_MAX_STREAMS];
+} strait_ctx_desc;
+
+/* Model: `weights` is a host pointer to a weight container ("STRW" v1: 48-byte header
+ * {magic, version, arch, n_tensors, hyper[8]}, 80-byte tensor entries {name[40], dtype, ndim,
+ * shape[4], offset, nbytes}, fp16 payloads; conv weights OIHW, linear weights [out,in],
+ * BatchNorm as separate gamma/beta/mean/var vectors).  The container is read during the call
+ * only.  Load folds BatchNorm (scale = gamma/sqrt(var+1e-5) in fp32; weight*scale rounded once
+ * to fp16; bias = beta - mean*scale kept fp32), re-lays weights for the kernels, uploads them
+ * and creates `n_instances` instances, each with pinned staging and device buffers sized for
+ * `max_batch` (Section 3, first paragraph after Figure 3; Section 4). */
+typedef struct {
+    const void* weights;
+    size_t weights_bytes;
+    int32_t max_batch;
+    int32_t n_instances;
+} strait_model_desc;
+
+/* Completion record of one batch (Section 5.1: latency runs from enqueue to the result being
+ * back in host memory; Section 3.2: measured H2D time; Section 3.3: measured kernel latency).
+ * Times in ms are device-side (hipEventElapsedTime); *_ns are host CLOCK_MONOTONIC. */
+typedef struct {
+    int32_t model_id, priority, batch, instance;
+    int64_t t_enqueue_ns;      /* host time at entry of strait_submit                       */
+    int64_t t_issued_ns;       /* host time when everything had been enqueued               */
+    int64_t t_done_ns;         /* host time the completion thread saw the D2H copy finish   */
+    float h2d_ms;              /* input copy                                                */
+    float kernel_ms;           /* first kernel start to last kernel end                     */
+    float d2h_ms;              /* output copy                                               */
+    float total_ms;            /* start of input copy to end of output copy                 */
+} strait_record;
+
+/* Per-layer accounting (pure query, valid after load). */
+typedef struct {
+    char name[40];
+    int32_t kind;              /* 0 conv/gemm (MFMA), 1 depthwise, 2 pool, 3 softmax, 4 layernorm,
+                                  5 attention, 6 pack                                       */
+    int64_t macs_per_sample;   /* multiply-accumulates per image / sequence (unmasked)      */
+    int64_t bytes_per_sample;  /* activation bytes read + written once, per image / sequence */
+    int64_t weight_bytes;      /* parameter bytes read once per launch                      */
+    int32_t gemm_m_per_sample, gemm_n, gemm_k;  /* implicit-GEMM shape (kind 0), else 0     */
+} strait_layer_info;
+
+const char* strait_last_error(void);
+int32_t strait_version(void);
+
+strait_status strait_ctx_create(const strait_ctx_desc* desc, strait_ctx** out);
+strait_status strait_ctx_destroy(strait_ctx* ctx);      /* E_BUSY while models are loaded   */
+
+strait_status strait_model_load(strait_ctx* ctx, const strait_model_desc* desc, strait_model** out);
+strait_status strait_model_free(strait_model* m);       /* E_BUSY with batches in flight    */
+
+/* Sizes of one batch's host input and output.
+ * CNN input : fp16 [batch][H][W][3].  CNN output: fp32 logits [batch][classes], then fp32
+ *             probabilities [batch][classes], then int32 top-1 [batch] (lowest index on ties).
+ * Encoder in: fp16 [batch][seq][hidden] (+ int32 valid_len[batch] passed separately);
+ *        out: fp16 hidden states [batch][seq][hidden], then int32 argmax over the features of
+ *             token 0 [batch]. */
+strait_status strait_model_io(const strait_model* m, int32_t batch, size_t* in_bytes, size_t* out_bytes);
+strait_status strait_model_info(const strait_model* m, int32_t* arch, int32_t* n_layers,
+                                int32_t* max_batch, int32_t* n_instances, int32_t hyper[8]);
+strait_status strait_model_layer(const strait_model* m, int32_t layer, strait_layer_info* out);
+
+/* Submit a batch at a priority level: picks an idle instance (E_BUSY if none -- never blocks),
+ * copies `host_in` into the instance's pinned buffer, enqueues H2D copy, kernel sequence and
+ * D2H copy without any host synchronisation, and returns a ticket.  `host_in` may be reused
+ * as soon as the call returns; `host_out` must stay valid until strait_wait returns.
+ * `valid_len` (host, int32[batch]) is required for the encoder and ignored otherwise. */
+strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch, const void* host_in,
+                            const int32_t* valid_len, void* host_out, strait_ticket* ticket);
+strait_status strait_poll(strait_ticket ticket, int32_t* done);
+/* Blocks until the batch is complete, fills `rec` (may be NULL) and releases the ticket and
+ * its instance. */
+strait_status strait_wait(strait_ticket ticket, strait_record* rec);
+
+/* Sub-steps on an explicit instance (0 <= instance < n_instances), for tests, profiling and
+ * throughput runs with the input already resident in device memory.  They do not take the
+ * instance from the pool: the caller must not mix them with strait_submit on the same model
+ * concurrently.  All are asynchronous on the priority's compute stream (copy_in: on a copy
+ * stream, with the compute stream made to wait for it); strait_sync waits for the instance. */
+strait_status strait_copy_in(strait_model* m, int32_t instance, strait_priority prio, int32_t batch,
+                             const void* host_in, const int32_t* valid_len);
+strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio, int32_t batch);
+strait_status strait_copy_out(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, void* host_out);
+strait_status strait_sync(strait_model* m, int32_t instance, strait_priority prio);
+/* Like strait_run, with a hipEvent pair around every layer; after an internal synchronise,
+ * layer_ms[i] (host, float[n_layers]) holds layer i's device time. */
+strait_status strait_run_timed(strait_model* m, int32_t instance, strait_priority prio, int32_t batch,
+                               float* layer_ms);
+/* Copies an intermediate activation (the output of layer `layer`) of the instance's last run
+ * to host memory as fp16; `bytes` must equal the layer's output size for `batch`. */
+strait_status strait_read_activation(strait_model* m, int32_t instance, int32_t layer, int32_t batch,
+                                     void* host_out, size_t bytes, size_t* needed);
+
+/* ---- kernel-level entry points: device pointers + stream -------------------------------
+ * Each is one launch of one of the library's kernels, for per-operator parity checks.
+ * All tensors fp16 unless noted.  `hp` != 0 raises the wave priority inside the kernel. */
+
+/* y[n,p,q,k] = act(bias[k] + sum_{r,s,c} x[n,p*stride+r-pad,q*stride+s-pad,c] * w[k,r,s,c] (+ res[n,p,q,k]))
+ * x [N,H,W,C], w [K][R][S][C] ("KRSC"), bias fp32 [K] or NULL, res [N,P,Q,K] or NULL, y [N,P,Q,K]
+ * (fp32 when out_f32 != 0).  The operator of Section 3.2 step (2) for convolution layers. */
+strait_status strait_k_conv2d(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                              const void* w_krsc, const float* bias, int32_t K, int32_t R, int32_t S,
+                              int32_t stride, int32_t pad, int32_t act, const void* res, void* y,
+                              int32_t out_f32, int32_t hp);
+/* Y[M,N] = act(X[M,K] W[N,K]^T + bias (+ res)); same kernel as the 1x1 convolution. */
+strait_status strait_k_gemm(void* stream, const void* x, const void* w, const float* bias, int32_t M,
+                            int32_t N, int32_t K, int32_t act, const void* res, void* y, int32_t out_f32,
+                            int32_t hp);
+/* Depthwise 3x3: y[n,p,q,c] = act(bias[c] + sum_{r,s} x[..,c] * w[r][s][c]); w fp16 [3][3][C]; C % 8 == 0. */
+strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                                 const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,
+                                 int32_t hp);
+/* Max pooling 3x3, stride 2, pad 1 (padding never wins); C % 8 == 0. */
+strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                                    void* y, int32_t hp);
+/* Global average pooling [N,HW,C] -> fp16 [N,C], fp32 accumulation; C % 8 == 0. */
+strait_status strait_k_global_avgpool(void* stream, const void* x, int32_t N, int32_t HW, int32_t C, void* y,
+                                      int32_t hp);
+/* Row softmax of fp32 logits [rows][n] -> fp32 probs, int32 top1 (argmax of the logits, lowest
+ * index on ties). */
+strait_status strait_k_softmax_top1(void* stream, const float* logits, int32_t rows, int32_t n, float* probs,
+                                    int32_t* top1, int32_t hp);
+/* LayerNorm over the last axis, biased variance, eps inside the square root:
+ * y = (x - mean)/sqrt(var + eps) * gamma + beta; x,y fp16 [rows][n], gamma/beta fp32; n % 8 == 0, n <= 8192. */
+strait_status strait_k_layernorm(void* stream, const void* x, const float* gamma, const float* beta,
+                                 int32_t rows, int32_t n, float eps, void* y, int32_t hp);
+/* Fused masked multi-head attention.  qkv fp16 [B][S][3*hidden] (Q | K | V along the last
+ * axis), valid_len int32 [B] (device), out fp16 [B][S][hidden]; head dim must be 64, S <= 128
+ * and S % 32 == 0.  Keys j >= valid_len[b] get probability exactly 0; query rows in 32-row
+ * blocks that lie entirely at or beyond valid_len[b] are written as zeros. */
+strait_status strait_k_attention(void* stream, const void* qkv, const int32_t* valid_len, int32_t B, int32_t S,
+                                 int32_t heads, void* out, int32_t hp);
+/* fp16 argmax over the first `n` features of row (b * row_stride) -> int32 top1[b]. */
+strait_status strait_k_argmax_f16(void* stream, const void* x, int32_t rows, int32_t n, int64_t row_stride,
+                                  int32_t* top1, int32_t hp);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRAIT_H */

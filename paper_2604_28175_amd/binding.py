@@ -1,0 +1,346 @@
+"""ctypes binding of libstrait.so: the same names as include/strait.h, argument marshalling only.
+
+PyTorch appears here for plumbing alone: it owns the HIP streams handed to the library and the
+device tensors passed to the kernel-level entry points.  There is no CPU fallback: if the
+library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libstrait.so")
+
+# PyTorch-ROCm ships its own copy of the HIP runtime.  It has to be in the process before
+# libstrait.so is opened, so that the library's dependency on libamdhip64.so.7 resolves to that
+# same copy: two HIP runtimes in one process do not share devices, streams or memory.
+import torch  # noqa: E402,F401
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(there is no fallback path)")
+lib = C.CDLL(LIB_PATH)
+
+OK, E_INVALID, E_HIP, E_FORMAT, E_NOMEM, E_SHAPE, E_BUSY, E_BATCH = 0, -1, -2, -3, -4, -5, -6, -7
+PRIO_HIGH, PRIO_LOW = 0, 1
+ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU = 0, 1, 2, 3
+MAX_STREAMS = 8
+
+
+class StraitError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"strait status {status}: {msg}")
+        self.status = status
+
+
+class CtxDesc(C.Structure):
+    _fields_ = [("device", C.c_int32), ("n_hp", C.c_int32), ("n_lp", C.c_int32), ("n_copy", C.c_int32),
+                ("hp_streams", C.c_void_p * MAX_STREAMS), ("lp_streams", C.c_void_p * MAX_STREAMS),
+                ("copy_streams", C.c_void_p * MAX_STREAMS)]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("weights", C.c_void_p), ("weights_bytes", C.c_size_t), ("max_batch", C.c_int32),
+                ("n_instances", C.c_int32)]
+
+
+class Record(C.Structure):
+    _fields_ = [("model_id", C.c_int32), ("priority", C.c_int32), ("batch", C.c_int32), ("instance", C.c_int32),
+                ("t_enqueue_ns", C.c_int64), ("t_issued_ns", C.c_int64), ("t_done_ns", C.c_int64),
+                ("h2d_ms", C.c_float), ("kernel_ms", C.c_float), ("d2h_ms", C.c_float), ("total_ms", C.c_float)]
+
+
+class LayerInfo(C.Structure):
+    _fields_ = [("name", C.c_char * 40), ("kind", C.c_int32), ("macs_per_sample", C.c_int64),
+                ("bytes_per_sample", C.c_int64), ("weight_bytes", C.c_int64),
+                ("gemm_m_per_sample", C.c_int32), ("gemm_n", C.c_int32), ("gemm_k", C.c_int32)]
+
+
+_vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+_SIGS = {
+    "strait_last_error": (C.c_char_p, []),
+    "strait_version": (_i32, []),
+    "strait_ctx_create": (_i32, [C.POINTER(CtxDesc), C.POINTER(_vp)]),
+    "strait_ctx_destroy": (_i32, [_vp]),
+    "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
+    "strait_model_free": (_i32, [_vp]),
+    "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
+    "strait_model_info": (_i32, [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32 * 8)]),
+    "strait_model_layer": (_i32, [_vp, _i32, C.POINTER(LayerInfo)]),
+    "strait_submit": (_i32, [_vp, _i32, _i32, _vp, _vp, _vp, C.POINTER(_vp)]),
+    "strait_poll": (_i32, [_vp, C.POINTER(_i32)]),
+    "strait_wait": (_i32, [_vp, C.POINTER(Record)]),
+    "strait_copy_in": (_i32, [_vp, _i32, _i32, _i32, _vp, _vp]),
+    "strait_run": (_i32, [_vp, _i32, _i32, _i32]),
+    "strait_copy_out": (_i32, [_vp, _i32, _i32, _i32, _vp]),
+    "strait_sync": (_i32, [_vp, _i32, _i32]),
+    "strait_run_timed": (_i32, [_vp, _i32, _i32, _i32, _vp]),
+    "strait_read_activation": (_i32, [_vp, _i32, _i32, _i32, _vp, _sz, C.POINTER(_sz)]),
+    "strait_k_conv2d": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
+    "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
+    "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
+    "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_global_avgpool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_softmax_top1": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _i32]),
+    "strait_k_layernorm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, C.c_float, _vp, _i32]),
+    "strait_k_attention": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_argmax_f16": (_i32, [_vp, _vp, _i32, _i32, _i64, _vp, _i32]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+EXPORTS = tuple(_SIGS.keys())
+
+
+def last_error() -> str:
+    return (lib.strait_last_error() or b"").decode()
+
+
+def _check(status: int):
+    if status != OK:
+        raise StraitError(status, last_error())
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_vp)
+
+
+def _dev(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class Context:
+    """strait_ctx over streams created through PyTorch (all at the default stream priority)."""
+
+    def __init__(self, device: int = 0, n_hp: int = 1, n_lp: int = 1, n_copy: int = 2):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("strait needs a GPU: no HIP device is visible (there is no CPU path)")
+        self.torch = torch
+        self.device = device
+        torch.cuda.set_device(device)
+        mk = lambda n: [torch.cuda.Stream(device=device) for _ in range(n)]
+        self.hp_streams, self.lp_streams, self.copy_streams = mk(n_hp), mk(n_lp), mk(n_copy)
+        d = CtxDesc()
+        d.device, d.n_hp, d.n_lp, d.n_copy = device, n_hp, n_lp, n_copy
+        for i, s in enumerate(self.hp_streams):
+            d.hp_streams[i] = s.cuda_stream
+        for i, s in enumerate(self.lp_streams):
+            d.lp_streams[i] = s.cuda_stream
+        for i, s in enumerate(self.copy_streams):
+            d.copy_streams[i] = s.cuda_stream
+        self.handle = _vp()
+        _check(lib.strait_ctx_create(C.byref(d), C.byref(self.handle)))
+
+    def load(self, weights: bytes, max_batch: int, n_instances: int = 1) -> "Model":
+        return Model(self, weights, max_batch, n_instances)
+
+    def close(self):
+        if self.handle:
+            _check(lib.strait_ctx_destroy(self.handle))
+            self.handle = _vp()
+
+
+class Model:
+    def __init__(self, ctx: Context, weights: bytes, max_batch: int, n_instances: int):
+        self.ctx = ctx
+        buf = (C.c_char * len(weights)).from_buffer_copy(weights)
+        d = ModelDesc(C.cast(buf, _vp), len(weights), max_batch, n_instances)
+        self.handle = _vp()
+        _check(lib.strait_model_load(ctx.handle, C.byref(d), C.byref(self.handle)))
+        arch, nl, mb, ni = _i32(), _i32(), _i32(), _i32()
+        hyper = (_i32 * 8)()
+        _check(lib.strait_model_info(self.handle, C.byref(arch), C.byref(nl), C.byref(mb), C.byref(ni), C.byref(hyper)))
+        self.arch, self.n_layers, self.max_batch, self.n_instances = arch.value, nl.value, mb.value, ni.value
+        self.hyper = tuple(hyper)
+        self._keep = {}
+
+    # ---- queries
+    def io_bytes(self, batch: int):
+        a, b = _sz(), _sz()
+        _check(lib.strait_model_io(self.handle, batch, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def layer(self, i: int) -> LayerInfo:
+        li = LayerInfo()
+        _check(lib.strait_model_layer(self.handle, i, C.byref(li)))
+        return li
+
+    def layers(self):
+        return [self.layer(i) for i in range(self.n_layers)]
+
+    # ---- output decoding (layout documented in strait.h)
+    def new_output(self, batch: int) -> np.ndarray:
+        return np.empty(self.io_bytes(batch)[1], dtype=np.uint8)
+
+    def decode(self, out: np.ndarray, batch: int):
+        if self.arch == 3:
+            _, hidden, _, _, seq = self.hyper[:5]
+            n = batch * seq * hidden
+            return {"hidden": out[:2 * n].view(np.float16).reshape(batch, seq, hidden),
+                    "top1": out[2 * n:2 * n + 4 * batch].view(np.int32)}
+        classes = self.hyper[3]
+        n = batch * classes
+        return {"logits": out[:4 * n].view(np.float32).reshape(batch, classes),
+                "probs": out[4 * n:8 * n].view(np.float32).reshape(batch, classes),
+                "top1": out[8 * n:8 * n + 4 * batch].view(np.int32)}
+
+    # ---- the served path
+    def submit(self, prio: int, x: np.ndarray, valid_len: Optional[np.ndarray], out: np.ndarray) -> int:
+        batch = x.shape[0]
+        assert x.dtype == np.float16 and x.flags.c_contiguous and out.flags.c_contiguous
+        if valid_len is not None:
+            valid_len = np.ascontiguousarray(valid_len, dtype=np.int32)
+        t = _vp()
+        _check(lib.strait_submit(self.handle, prio, batch, _np_ptr(x), _np_ptr(valid_len), _np_ptr(out), C.byref(t)))
+        self._keep[t.value] = (x, valid_len, out)
+        return t.value
+
+    def try_submit(self, prio, x, valid_len, out):
+        """Like submit, but returns None instead of raising when every instance is busy."""
+        try:
+            return self.submit(prio, x, valid_len, out)
+        except StraitError as e:
+            if e.status == E_BUSY:
+                return None
+            raise
+
+    def poll(self, ticket: int) -> bool:
+        d = _i32()
+        _check(lib.strait_poll(_vp(ticket), C.byref(d)))
+        return bool(d.value)
+
+    def wait(self, ticket: int) -> Record:
+        r = Record()
+        st = lib.strait_wait(_vp(ticket), C.byref(r))
+        self._keep.pop(ticket, None)
+        _check(st)
+        return r
+
+    def infer(self, x: np.ndarray, valid_len=None, prio: int = PRIO_HIGH):
+        out = self.new_output(x.shape[0])
+        rec = self.wait(self.submit(prio, x, valid_len, out))
+        return self.decode(out, x.shape[0]), rec
+
+    # ---- sub-steps
+    def copy_in(self, instance, prio, x, valid_len=None):
+        if valid_len is not None:
+            valid_len = np.ascontiguousarray(valid_len, dtype=np.int32)
+        _check(lib.strait_copy_in(self.handle, instance, prio, x.shape[0], _np_ptr(x), _np_ptr(valid_len)))
+
+    def run(self, instance, prio, batch):
+        _check(lib.strait_run(self.handle, instance, prio, batch))
+
+    def copy_out(self, instance, prio, batch) -> np.ndarray:
+        out = self.new_output(batch)
+        _check(lib.strait_copy_out(self.handle, instance, prio, batch, _np_ptr(out)))
+        return out
+
+    def sync(self, instance, prio):
+        _check(lib.strait_sync(self.handle, instance, prio))
+
+    def run_timed(self, instance, prio, batch) -> np.ndarray:
+        ms = np.zeros(self.n_layers, dtype=np.float32)
+        _check(lib.strait_run_timed(self.handle, instance, prio, batch, _np_ptr(ms)))
+        return ms
+
+    def read_activation(self, instance, layer, batch) -> np.ndarray:
+        need = _sz()
+        _check(lib.strait_read_activation(self.handle, instance, layer, batch, None, 0, C.byref(need)))
+        out = np.empty(need.value // 2, dtype=np.float16)
+        _check(lib.strait_read_activation(self.handle, instance, layer, batch, _np_ptr(out), need.value, None))
+        return out
+
+    def free(self):
+        if self.handle:
+            _check(lib.strait_model_free(self.handle))
+            self.handle = _vp()
+
+
+# ---- kernel-level entry points on torch device tensors ---------------------------------------
+
+def _stream(stream=None) -> int:
+    import torch
+    return (stream or torch.cuda.current_stream()).cuda_stream
+
+
+def k_conv2d(x, w_krsc, bias, stride, pad, act=ACT_NONE, res=None, out_f32=False, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    k, r, s, c2 = w_krsc.shape
+    assert c2 == c
+    p, q = (h + 2 * pad - r) // stride + 1, (w + 2 * pad - s) // stride + 1
+    y = torch.empty((n, p, q, k), dtype=torch.float32 if out_f32 else torch.float16, device=x.device)
+    _check(lib.strait_k_conv2d(_stream(stream), _dev(x), n, h, w, c, _dev(w_krsc), _dev(bias), k, r, s, stride, pad,
+                               act, _dev(res), _dev(y), int(out_f32), hp))
+    return y
+
+
+def k_gemm(x, w, bias, act=ACT_NONE, res=None, out_f32=False, hp=0, stream=None):
+    import torch
+    m, k = x.shape
+    n = w.shape[0]
+    y = torch.empty((m, n), dtype=torch.float32 if out_f32 else torch.float16, device=x.device)
+    _check(lib.strait_k_gemm(_stream(stream), _dev(x), _dev(w), _dev(bias), m, n, k, act, _dev(res), _dev(y), int(out_f32), hp))
+    return y
+
+
+def k_dwconv3x3(x, w_rsc, bias, stride, act=ACT_NONE, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    p, q = (h - 1) // stride + 1, (w - 1) // stride + 1
+    y = torch.empty((n, p, q, c), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_dwconv3x3(_stream(stream), _dev(x), n, h, w, c, _dev(w_rsc), _dev(bias), stride, act, _dev(y), hp))
+    return y
+
+
+def k_maxpool3x3s2(x, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_maxpool3x3s2(_stream(stream), _dev(x), n, h, w, c, _dev(y), hp))
+    return y
+
+
+def k_global_avgpool(x, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    y = torch.empty((n, c), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_global_avgpool(_stream(stream), _dev(x), n, h * w, c, _dev(y), hp))
+    return y
+
+
+def k_softmax_top1(logits, hp=0, stream=None):
+    import torch
+    rows, n = logits.shape
+    probs = torch.empty_like(logits)
+    top1 = torch.empty((rows,), dtype=torch.int32, device=logits.device)
+    _check(lib.strait_k_softmax_top1(_stream(stream), _dev(logits), rows, n, _dev(probs), _dev(top1), hp))
+    return probs, top1
+
+
+def k_layernorm(x, gamma, beta, eps, hp=0, stream=None):
+    import torch
+    rows, n = x.shape
+    y = torch.empty_like(x)
+    _check(lib.strait_k_layernorm(_stream(stream), _dev(x), _dev(gamma), _dev(beta), rows, n, eps, _dev(y), hp))
+    return y
+
+
+def k_attention(qkv, valid_len, heads, hp=0, stream=None):
+    import torch
+    b, s, h3 = qkv.shape
+    out = torch.empty((b, s, h3 // 3), dtype=torch.float16, device=qkv.device)
+    _check(lib.strait_k_attention(_stream(stream), _dev(qkv), _dev(valid_len), b, s, heads, _dev(out), hp))
+    return out
+
+
+def k_argmax_f16(x, n, row_stride, rows, hp=0, stream=None):
+    import torch
+    top1 = torch.empty((rows,), dtype=torch.int32, device=x.device)
+    _check(lib.strait_k_argmax_f16(_stream(stream), _dev(x), rows, n, row_stride, _dev(top1), hp))
+    return top1

@@ -1,0 +1,485 @@
+// C ABI (strait.h): contexts, model instances, dual-priority submission, completion records.
+//
+// A submitted batch follows the paper's three steps (Section 3.2): input into the instance's
+// pinned buffer and an asynchronous host-to-device copy on a copy stream; the kernel sequence
+// on the compute stream that belongs to the batch's priority level (Section 3.1), made to wait
+// for the copy through an event; the device-to-host copy of the result into pinned memory.
+// Nothing synchronises with the host in between.  One completion thread per compute stream
+// waits for batches in issue order, stamps the host completion time (Section 5.1: latency ends
+// when the result is back in host memory), reads the event timings that Strait's predictor
+// would be fed (measured H2D time, measured kernel latency) and hands the result over.
+#include <time.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "runtime.hpp"
+
+namespace strait {
+const char* last_error();
+}
+using namespace strait;
+
+#define HIP_TRY(expr)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return STRAIT_E_HIP; } \
+    } while (0)
+
+struct strait_ctx : Context {};
+struct strait_model : Model {};
+struct strait_ticket_s : Ticket {};
+
+static int64_t now_ns() {
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (int64_t)ts.tv_sec * 1000000000LL + ts.tv_nsec;
+}
+
+static void worker_loop(Context* ctx, StreamWorker* w) {
+    (void)hipSetDevice(ctx->device);
+    for (;;) {
+        Ticket* t = nullptr;
+        {
+            std::unique_lock<std::mutex> lk(ctx->mu);
+            ctx->cv_work.wait(lk, [&] { return ctx->stop || !w->q.empty(); });
+            if (w->q.empty()) return;           // stop requested and nothing left
+            t = w->q.front();
+            w->q.pop_front();
+        }
+        Instance& in = t->model->inst[t->instance];
+        hipError_t e = hipEventSynchronize(in.ev_done);
+        const int64_t done = now_ns();
+        int status = 0;
+        if (e != hipSuccess) status = STRAIT_E_HIP;
+        else {
+            memcpy(t->host_out, in.pinned_out, t->model->out_bytes(t->batch));
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, in.ev_h2d0, in.ev_h2d1) == hipSuccess) t->rec.h2d_ms = ms;
+            if (hipEventElapsedTime(&ms, in.ev_k0, in.ev_k1) == hipSuccess) t->rec.kernel_ms = ms;
+            if (hipEventElapsedTime(&ms, in.ev_k1, in.ev_done) == hipSuccess) t->rec.d2h_ms = ms;
+            if (hipEventElapsedTime(&ms, in.ev_h2d0, in.ev_done) == hipSuccess) t->rec.total_ms = ms;
+        }
+        {
+            std::lock_guard<std::mutex> lk(ctx->mu);
+            t->rec.t_done_ns = done;
+            t->status = status;
+            t->done = true;
+        }
+        ctx->cv_done.notify_all();
+    }
+}
+
+extern "C" {
+
+const char* strait_last_error(void) { return strait::last_error(); }
+int32_t strait_version(void) { return 1; }
+
+strait_status strait_ctx_create(const strait_ctx_desc* d, strait_ctx** out) {
+    if (!d || !out) { set_error("ctx_create: null argument"); return STRAIT_E_INVALID; }
+    if (d->n_hp < 1 || d->n_lp < 1 || d->n_copy < 1 || d->n_hp > STRAIT_MAX_STREAMS || d->n_lp > STRAIT_MAX_STREAMS ||
+        d->n_copy > STRAIT_MAX_STREAMS) { set_error("ctx_create: stream counts must be in 1..%d", STRAIT_MAX_STREAMS); return STRAIT_E_INVALID; }
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (d->device < 0 || d->device >= ndev) { set_error("ctx_create: device %d not present (%d devices)", d->device, ndev); return STRAIT_E_INVALID; }
+    HIP_TRY(hipSetDevice(d->device));
+    strait_ctx* c = new (std::nothrow) strait_ctx();
+    if (!c) { set_error("out of host memory"); return STRAIT_E_NOMEM; }
+    c->device = d->device;
+    for (int i = 0; i < d->n_hp; ++i) c->hp.push_back((hipStream_t)d->hp_streams[i]);
+    for (int i = 0; i < d->n_lp; ++i) c->lp.push_back((hipStream_t)d->lp_streams[i]);
+    for (int i = 0; i < d->n_copy; ++i) c->copy.push_back((hipStream_t)d->copy_streams[i]);
+    for (size_t i = 0; i < c->hp.size() + c->lp.size(); ++i) {
+        StreamWorker* w = new StreamWorker();
+        w->stream = i < c->hp.size() ? c->hp[i] : c->lp[i - c->hp.size()];
+        c->workers.push_back(w);
+    }
+    for (StreamWorker* w : c->workers) w->th = std::thread(worker_loop, (Context*)c, w);
+    *out = c;
+    return STRAIT_OK;
+}
+
+strait_status strait_ctx_destroy(strait_ctx* c) {
+    if (!c) { set_error("ctx_destroy: null"); return STRAIT_E_INVALID; }
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (c->n_models > 0) { set_error("ctx_destroy: %d models still loaded", c->n_models); return STRAIT_E_BUSY; }
+        c->stop = true;
+    }
+    c->cv_work.notify_all();
+    for (StreamWorker* w : c->workers) { if (w->th.joinable()) w->th.join(); delete w; }
+    delete c;
+    return STRAIT_OK;
+}
+
+static void free_instance(Instance& in) {
+    if (in.pinned_in) (void)hipHostFree(in.pinned_in);
+    if (in.pinned_out) (void)hipHostFree(in.pinned_out);
+    if (in.dev_in) (void)hipFree(in.dev_in);
+    if (in.dev_out) (void)hipFree(in.dev_out);
+    if (in.dev_valid) (void)hipFree(in.dev_valid);
+    for (void* b : in.bufs) if (b) (void)hipFree(b);
+    hipEvent_t evs[5] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done};
+    for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : in.layer_ev) if (e) (void)hipEventDestroy(e);
+    in = Instance();
+}
+
+static void free_model(strait_model* m) {
+    for (Instance& in : m->inst) free_instance(in);
+    for (void* d : m->dev_allocs) (void)hipFree(d);
+    delete m;
+}
+
+strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strait_model** out) {
+    if (!c || !d || !out || !d->weights) { set_error("model_load: null argument"); return STRAIT_E_INVALID; }
+    if (d->max_batch < 1 || d->max_batch > 4096 || d->n_instances < 1 || d->n_instances > 64) {
+        set_error("model_load: max_batch must be in 1..4096 and n_instances in 1..64"); return STRAIT_E_INVALID;
+    }
+    HIP_TRY(hipSetDevice(c->device));
+    strait_model* m = new (std::nothrow) strait_model();
+    if (!m) { set_error("out of host memory"); return STRAIT_E_NOMEM; }
+    m->ctx = c;
+    m->max_batch = d->max_batch;
+    int rc = build_plan(*m, d->weights, d->weights_bytes);
+    if (rc) { free_model(m); return rc; }
+    m->inst.resize(d->n_instances);
+    const size_t inb = (m->in_bytes(d->max_batch) + 255) / 256 * 256, outb = (m->out_bytes(d->max_batch) + 255) / 256 * 256;
+    for (Instance& in : m->inst) {
+        bool ok = hipHostMalloc(&in.pinned_in, inb + (size_t)d->max_batch * 4, hipHostMallocDefault) == hipSuccess &&
+                  hipHostMalloc(&in.pinned_out, outb, hipHostMallocDefault) == hipSuccess &&
+                  hipMalloc(&in.dev_in, inb) == hipSuccess && hipMalloc(&in.dev_out, outb) == hipSuccess &&
+                  hipMalloc((void**)&in.dev_valid, (size_t)d->max_batch * 4 + 256) == hipSuccess;
+        for (size_t i = 0; ok && i < m->buf_elems.size(); ++i) {
+            void* b = nullptr;
+            const size_t bytes = (m->buf_elems[i] * 2 * (size_t)d->max_batch + 255) / 256 * 256;
+            ok = hipMalloc(&b, bytes) == hipSuccess;
+            in.bufs.push_back(b);
+        }
+        ok = ok && hipEventCreate(&in.ev_h2d0) == hipSuccess && hipEventCreate(&in.ev_h2d1) == hipSuccess &&
+             hipEventCreate(&in.ev_k0) == hipSuccess && hipEventCreate(&in.ev_k1) == hipSuccess &&
+             hipEventCreate(&in.ev_done) == hipSuccess;
+        if (ok) {
+            in.layer_ev.resize(m->ops.size() + 1, nullptr);
+            for (hipEvent_t& e : in.layer_ev) ok = ok && hipEventCreate(&e) == hipSuccess;
+        }
+        if (!ok) {
+            (void)hipGetLastError();
+            set_error("model_load: allocating an instance (%zu B in, %zu B out, %zu activation buffers) failed", inb, outb, m->buf_elems.size());
+            free_model(m);
+            return STRAIT_E_NOMEM;
+        }
+        // valid lengths default to the full sequence
+        if (m->arch == STRAIT_ARCH_ENCODER) {
+            std::vector<int32_t> full(d->max_batch, m->seq);
+            HIP_TRY(hipMemcpy(in.dev_valid, full.data(), full.size() * 4, hipMemcpyHostToDevice));
+        }
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        m->id = c->next_model_id++;
+        c->n_models++;
+    }
+    *out = m;
+    return STRAIT_OK;
+}
+
+strait_status strait_model_free(strait_model* m) {
+    if (!m) { set_error("model_free: null"); return STRAIT_E_INVALID; }
+    {
+        std::lock_guard<std::mutex> lk(m->mu);
+        if (m->in_flight > 0) { set_error("model_free: %d batches in flight", m->in_flight); return STRAIT_E_BUSY; }
+    }
+    Context* c = m->ctx;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    free_model(m);
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->n_models--;
+    return STRAIT_OK;
+}
+
+strait_status strait_model_io(const strait_model* m, int32_t batch, size_t* in_bytes, size_t* out_bytes) {
+    if (!m) { set_error("model_io: null"); return STRAIT_E_INVALID; }
+    if (batch < 1 || batch > m->max_batch) { set_error("batch %d outside 1..%d", batch, m->max_batch); return STRAIT_E_BATCH; }
+    if (in_bytes) *in_bytes = m->in_bytes(batch);
+    if (out_bytes) *out_bytes = m->out_bytes(batch);
+    return STRAIT_OK;
+}
+
+strait_status strait_model_info(const strait_model* m, int32_t* arch, int32_t* n_layers, int32_t* max_batch,
+                                int32_t* n_instances, int32_t hyper[8]) {
+    if (!m) { set_error("model_info: null"); return STRAIT_E_INVALID; }
+    if (arch) *arch = m->arch;
+    if (n_layers) *n_layers = (int32_t)m->ops.size();
+    if (max_batch) *max_batch = m->max_batch;
+    if (n_instances) *n_instances = (int32_t)m->inst.size();
+    if (hyper) for (int i = 0; i < 8; ++i) hyper[i] = m->hyper[i];
+    return STRAIT_OK;
+}
+
+strait_status strait_model_layer(const strait_model* m, int32_t layer, strait_layer_info* out) {
+    if (!m || !out) { set_error("model_layer: null"); return STRAIT_E_INVALID; }
+    if (layer < 0 || layer >= (int)m->ops.size()) { set_error("layer %d outside 0..%zu", layer, m->ops.size() - 1); return STRAIT_E_INVALID; }
+    *out = m->ops[layer].info;
+    return STRAIT_OK;
+}
+
+static int check_call(strait_model* m, int instance, int prio, int batch) {
+    if (!m) { set_error("null model"); return STRAIT_E_INVALID; }
+    if (instance < 0 || instance >= (int)m->inst.size()) { set_error("instance %d outside 0..%zu", instance, m->inst.size() - 1); return STRAIT_E_INVALID; }
+    if (prio != STRAIT_PRIO_HIGH && prio != STRAIT_PRIO_LOW) { set_error("priority must be STRAIT_PRIO_HIGH or STRAIT_PRIO_LOW"); return STRAIT_E_INVALID; }
+    if (batch < 1 || batch > m->max_batch) { set_error("batch %d outside 1..%d", batch, m->max_batch); return STRAIT_E_BATCH; }
+    return 0;
+}
+
+static hipStream_t compute_stream(Context* c, int prio, int instance) {
+    return prio == STRAIT_PRIO_HIGH ? c->hp[instance % c->hp.size()] : c->lp[instance % c->lp.size()];
+}
+
+static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* host_in, const int32_t* valid_len,
+                       hipStream_t cs, hipStream_t s) {
+    const size_t inb = m->in_bytes(batch);
+    memcpy(in.pinned_in, host_in, inb);
+    HIP_TRY(hipEventRecord(in.ev_h2d0, cs));
+    HIP_TRY(hipMemcpyAsync(in.dev_in, in.pinned_in, inb, hipMemcpyHostToDevice, cs));
+    if (m->arch == STRAIT_ARCH_ENCODER) {
+        const size_t off = (m->in_bytes(m->max_batch) + 255) / 256 * 256;
+        int32_t* pv = (int32_t*)((char*)in.pinned_in + off);
+        for (int i = 0; i < batch; ++i) pv[i] = valid_len[i] < 0 ? 0 : (valid_len[i] > m->seq ? m->seq : valid_len[i]);
+        HIP_TRY(hipMemcpyAsync(in.dev_valid, pv, (size_t)batch * 4, hipMemcpyHostToDevice, cs));
+    }
+    HIP_TRY(hipEventRecord(in.ev_h2d1, cs));
+    HIP_TRY(hipStreamWaitEvent(s, in.ev_h2d1, 0));
+    return 0;
+}
+
+strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch, const void* host_in,
+                            const int32_t* valid_len, void* host_out, strait_ticket* ticket) {
+    const int64_t t_enq = now_ns();
+    int rc = check_call(m, 0, prio, batch);
+    if (rc) return rc;
+    if (!host_in || !host_out || !ticket) { set_error("submit: null argument"); return STRAIT_E_INVALID; }
+    if (m->arch == STRAIT_ARCH_ENCODER && !valid_len) { set_error("submit: the encoder needs valid_len"); return STRAIT_E_INVALID; }
+    Context* c = m->ctx;
+    int idx = -1;
+    {
+        std::lock_guard<std::mutex> lk(m->mu);
+        for (size_t i = 0; i < m->inst.size(); ++i)
+            if (!m->inst[i].busy) { idx = (int)i; break; }
+        if (idx < 0) { set_error("submit: all %zu instances busy", m->inst.size()); return STRAIT_E_BUSY; }
+        m->inst[idx].busy = true;
+        m->in_flight++;
+    }
+    auto release = [&]() { std::lock_guard<std::mutex> lk(m->mu); m->inst[idx].busy = false; m->in_flight--; };
+    strait_ticket_s* t = new (std::nothrow) strait_ticket_s();
+    if (!t) { release(); set_error("out of host memory"); return STRAIT_E_NOMEM; }
+    Instance& in = m->inst[idx];
+    unsigned si, ci;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        si = prio == STRAIT_PRIO_HIGH ? c->n_hp_sub++ : c->n_lp_sub++;
+        ci = c->n_copy_sub++;
+    }
+    const size_t widx = prio == STRAIT_PRIO_HIGH ? si % c->hp.size() : c->hp.size() + si % c->lp.size();
+    hipStream_t s = c->workers[widx]->stream;
+    hipStream_t cs = c->copy[ci % c->copy.size()];
+    rc = hipSetDevice(c->device) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (!rc) rc = enqueue_h2d(m, in, batch, host_in, valid_len, cs, s);
+    if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (!rc) rc = run_plan(*m, in, batch, s, prio == STRAIT_PRIO_HIGH, -1, false);
+    if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (rc) {
+        if (rc == STRAIT_E_HIP && !strait::last_error()[0]) set_error("submit: a HIP call failed");
+        (void)hipStreamSynchronize(s);
+        (void)hipStreamSynchronize(cs);
+        release();
+        delete t;
+        return rc;
+    }
+    t->model = m; t->instance = idx; t->prio = prio; t->batch = batch; t->host_out = host_out;
+    t->rec.model_id = m->id; t->rec.priority = prio; t->rec.batch = batch; t->rec.instance = idx;
+    t->rec.t_enqueue_ns = t_enq;
+    t->rec.t_issued_ns = now_ns();
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->workers[widx]->q.push_back(t);
+    }
+    c->cv_work.notify_all();
+    *ticket = t;
+    return STRAIT_OK;
+}
+
+strait_status strait_poll(strait_ticket t, int32_t* done) {
+    if (!t || !done) { set_error("poll: null argument"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(t->model->ctx->mu);
+    *done = t->done ? 1 : 0;
+    return STRAIT_OK;
+}
+
+strait_status strait_wait(strait_ticket t, strait_record* rec) {
+    if (!t) { set_error("wait: null ticket"); return STRAIT_E_INVALID; }
+    Model* m = t->model;
+    Context* c = m->ctx;
+    {
+        std::unique_lock<std::mutex> lk(c->mu);
+        c->cv_done.wait(lk, [&] { return t->done; });
+    }
+    if (rec) *rec = t->rec;
+    const int status = t->status;
+    {
+        std::lock_guard<std::mutex> lk(m->mu);
+        m->inst[t->instance].busy = false;
+        m->in_flight--;
+    }
+    delete t;
+    if (status) { set_error("wait: the batch failed on the device"); return status; }
+    return STRAIT_OK;
+}
+
+strait_status strait_copy_in(strait_model* m, int32_t instance, strait_priority prio, int32_t batch,
+                             const void* host_in, const int32_t* valid_len) {
+    int rc = check_call(m, instance, prio, batch);
+    if (rc) return rc;
+    if (!host_in) { set_error("copy_in: null input"); return STRAIT_E_INVALID; }
+    if (m->arch == STRAIT_ARCH_ENCODER && !valid_len) { set_error("copy_in: the encoder needs valid_len"); return STRAIT_E_INVALID; }
+    Context* c = m->ctx;
+    HIP_TRY(hipSetDevice(c->device));
+    return enqueue_h2d(m, m->inst[instance], batch, host_in, valid_len, c->copy[instance % c->copy.size()], compute_stream(c, prio, instance));
+}
+
+strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio, int32_t batch) {
+    int rc = check_call(m, instance, prio, batch);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(m->ctx->device));
+    return run_plan(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), prio == STRAIT_PRIO_HIGH, -1, false);
+}
+
+strait_status strait_copy_out(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, void* host_out) {
+    int rc = check_call(m, instance, prio, batch);
+    if (rc) return rc;
+    if (!host_out) { set_error("copy_out: null output"); return STRAIT_E_INVALID; }
+    Instance& in = m->inst[instance];
+    hipStream_t s = compute_stream(m->ctx, prio, instance);
+    HIP_TRY(hipSetDevice(m->ctx->device));
+    HIP_TRY(hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    memcpy(host_out, in.pinned_out, m->out_bytes(batch));
+    return STRAIT_OK;
+}
+
+strait_status strait_sync(strait_model* m, int32_t instance, strait_priority prio) {
+    int rc = check_call(m, instance, prio, 1);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(m->ctx->device));
+    HIP_TRY(hipStreamSynchronize(compute_stream(m->ctx, prio, instance)));
+    return STRAIT_OK;
+}
+
+strait_status strait_run_timed(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, float* layer_ms) {
+    int rc = check_call(m, instance, prio, batch);
+    if (rc) return rc;
+    if (!layer_ms) { set_error("run_timed: null output"); return STRAIT_E_INVALID; }
+    Instance& in = m->inst[instance];
+    hipStream_t s = compute_stream(m->ctx, prio, instance);
+    HIP_TRY(hipSetDevice(m->ctx->device));
+    rc = run_plan(*m, in, batch, s, prio == STRAIT_PRIO_HIGH, -1, true);
+    if (rc) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    for (size_t i = 0; i < m->ops.size(); ++i) HIP_TRY(hipEventElapsedTime(&layer_ms[i], in.layer_ev[i], in.layer_ev[i + 1]));
+    return STRAIT_OK;
+}
+
+strait_status strait_read_activation(strait_model* m, int32_t instance, int32_t layer, int32_t batch, void* host_out,
+                                     size_t bytes, size_t* needed) {
+    int rc = check_call(m, instance, STRAIT_PRIO_LOW, batch);
+    if (rc) return rc;
+    if (layer < 0 || layer >= (int)m->ops.size()) { set_error("layer %d outside 0..%zu", layer, m->ops.size() - 1); return STRAIT_E_INVALID; }
+    const Op& op = m->ops[layer];
+    if (op.out < 0) { set_error("layer %d ('%s') writes to the output buffer; use copy_out", layer, op.name.c_str()); return STRAIT_E_INVALID; }
+    const size_t need = (size_t)batch * op.P * op.Q * op.K * 2;
+    if (needed) *needed = need;
+    if (!host_out) return STRAIT_OK;
+    if (bytes != need) { set_error("read_activation: layer '%s' holds %zu bytes for batch %d, caller gave %zu", op.name.c_str(), need, batch, bytes); return STRAIT_E_INVALID; }
+    Instance& in = m->inst[instance];
+    hipStream_t s = compute_stream(m->ctx, STRAIT_PRIO_LOW, instance);
+    HIP_TRY(hipSetDevice(m->ctx->device));
+    rc = run_plan(*m, in, batch, s, 0, layer, false);     // re-run the prefix: later layers reuse buffers
+    if (rc) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipMemcpy(host_out, in.bufs[op.out], need, hipMemcpyDeviceToHost));
+    return STRAIT_OK;
+}
+
+// ---- kernel-level entry points -----------------------------------------------------------------
+
+strait_status strait_k_conv2d(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                              const void* w_krsc, const float* bias, int32_t K, int32_t R, int32_t S, int32_t stride,
+                              int32_t pad, int32_t act, const void* res, void* y, int32_t out_f32, int32_t hp) {
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 ||
+        H + 2 * pad < R || W + 2 * pad < S) { set_error("conv2d: invalid shape"); return STRAIT_E_SHAPE; }
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    if ((long long)N * P * Q > 0x7fffffffLL || (long long)R * S * C > 0x7fffffffLL) { set_error("conv2d: too large"); return STRAIT_E_SHAPE; }
+    ConvParams p{};
+    p.x = (const half_t*)x; p.bias = bias; p.res = (const half_t*)res; p.y = y;
+    p.M = N * P * Q; p.PQ = P * Q; p.Q = Q; p.H = H; p.W = W; p.C = C; p.R = R; p.S = S;
+    p.stride_h = p.stride_w = stride; p.pad_h = p.pad_w = pad;
+    p.sN = (long long)H * W * C; p.sH = W * C; p.sW = C;
+    p.Kg = R * S * C; p.Cout = K; p.ldy = K; p.act = act; p.out_f32 = out_f32; p.hp = hp;
+    void* tmp = nullptr;
+    if (p.Kg % 8 == 0) { p.w = (const half_t*)w_krsc; p.ldw = p.Kg; }
+    else {
+        // rows padded with zeros to a multiple of 8 elements, as the kernel's 16-byte weight loads need
+        p.ldw = (p.Kg + 7) / 8 * 8;
+        HIP_TRY(hipMalloc(&tmp, (size_t)K * p.ldw * 2));
+        hipError_t e = hipMemsetAsync(tmp, 0, (size_t)K * p.ldw * 2, (hipStream_t)stream);
+        if (e == hipSuccess) e = hipMemcpy2DAsync(tmp, (size_t)p.ldw * 2, w_krsc, (size_t)p.Kg * 2, (size_t)p.Kg * 2, K, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+        if (e != hipSuccess) { (void)hipFree(tmp); set_error("conv2d: padding the weights failed: %s", hipGetErrorString(e)); return STRAIT_E_HIP; }
+        p.w = (const half_t*)tmp;
+    }
+    int rc = launch_conv(p, (hipStream_t)stream);
+    if (tmp) { (void)hipStreamSynchronize((hipStream_t)stream); (void)hipFree(tmp); }
+    return rc;
+}
+
+strait_status strait_k_gemm(void* stream, const void* x, const void* w, const float* bias, int32_t M, int32_t N,
+                            int32_t K, int32_t act, const void* res, void* y, int32_t out_f32, int32_t hp) {
+    if (M <= 0 || N <= 0 || K <= 0 || K % 8 != 0) { set_error("gemm: needs positive sizes and K %% 8 == 0"); return STRAIT_E_SHAPE; }
+    ConvParams p{};
+    p.x = (const half_t*)x; p.w = (const half_t*)w; p.bias = bias; p.res = (const half_t*)res; p.y = y;
+    p.M = M; p.PQ = 1; p.Q = 1; p.H = 1; p.W = 1; p.C = K; p.R = 1; p.S = 1;
+    p.stride_h = p.stride_w = 1; p.pad_h = p.pad_w = 0;
+    p.sN = K; p.sH = K; p.sW = K; p.Kg = K; p.ldw = K; p.Cout = N; p.ldy = N; p.act = act; p.out_f32 = out_f32; p.hp = hp;
+    return launch_conv(p, (hipStream_t)stream);
+}
+
+strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                                 const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y, int32_t hp) {
+    return launch_dwconv3x3((const half_t*)x, N, H, W, C, (const half_t*)w_rsc, bias, stride, act, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
+    return launch_maxpool3x3s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_global_avgpool(void* stream, const void* x, int32_t N, int32_t HW, int32_t C, void* y, int32_t hp) {
+    return launch_global_avgpool((const half_t*)x, N, HW, C, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_softmax_top1(void* stream, const float* logits, int32_t rows, int32_t n, float* probs, int32_t* top1, int32_t hp) {
+    return launch_softmax_top1(logits, rows, n, probs, top1, hp, (hipStream_t)stream);
+}
+strait_status strait_k_layernorm(void* stream, const void* x, const float* gamma, const float* beta, int32_t rows,
+                                 int32_t n, float eps, void* y, int32_t hp) {
+    return launch_layernorm((const half_t*)x, gamma, beta, rows, n, eps, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_attention(void* stream, const void* qkv, const int32_t* valid_len, int32_t B, int32_t S,
+                                 int32_t heads, void* out, int32_t hp) {
+    return launch_attention((const half_t*)qkv, valid_len, B, S, heads, (half_t*)out, hp, (hipStream_t)stream);
+}
+strait_status strait_k_argmax_f16(void* stream, const void* x, int32_t rows, int32_t n, int64_t row_stride, int32_t* top1, int32_t hp) {
+    return launch_argmax_f16((const half_t*)x, rows, n, row_stride, top1, hp, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,388 @@
+// Bandwidth-bound kernels of the served models for gfx950: input packing, depthwise 3x3
+// convolution, pooling, softmax + top-1, LayerNorm, argmax.  (Paper Section 3.2 step (2): the
+// kernel sequence of a batch; these are its non-GEMM members.)
+//
+// None of these is a contraction worth MFMA: each reads its operands once from HBM/L2 and
+// writes its result once, so the design rule is 16-byte accesses that are contiguous across
+// the lanes of a wavefront (the channel axis of NHWC), fp32 arithmetic in registers, and
+// enough workgroups (>> 256) to cover the chip.
+#include "kernels.hpp"
+
+namespace strait {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+#define STRAIT_CHECK_LAUNCH(what)                                                   \
+    do {                                                                            \
+        hipError_t e_ = hipGetLastError();                                          \
+        if (e_ != hipSuccess) { set_error(what ": %s", hipGetErrorString(e_)); return -2; } \
+    } while (0)
+
+__device__ __forceinline__ float act_f(float v, int act) {
+    if (act == ACT_RELU) return fmaxf(v, 0.f);
+    if (act == ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// fill
+__global__ void fill_zero_kernel(uint4* p, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += step) p[i] = make_uint4(0, 0, 0, 0);
+}
+int launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return 0;
+    if ((reinterpret_cast<uintptr_t>(p) & 15) || (bytes & 15)) { set_error("fill: 16-byte alignment required"); return -1; }
+    const size_t n16 = bytes / 16;
+    unsigned blocks = (unsigned)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, (uint4*)p, n16);
+    STRAIT_CHECK_LAUNCH("fill");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// pack: [N][H][W][C] (C <= Cpad, Cpad in {4, 8}) -> zero-bordered [N][Hp][Wp][Cpad].
+// One thread per output pixel.
+template <int CPAD>
+__global__ void __launch_bounds__(256) pack_input_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
+                                                          half_t* __restrict__ y, int Hp, int Wp, int pt, int pl, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const long long total = (long long)N * Hp * Wp;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int wp = (int)(i % Wp);
+    const long long t = i / Wp;
+    const int hpix = (int)(t % Hp);
+    const int n = (int)(t / Hp);
+    const int h = hpix - pt, w = wp - pl;
+    _Float16 v[CPAD];
+#pragma unroll
+    for (int c = 0; c < CPAD; ++c) v[c] = (half_t)0;
+    if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+        const half_t* src = x + (((long long)n * H + h) * W + w) * C;
+#pragma unroll
+        for (int c = 0; c < CPAD; ++c)
+            if (c < C) v[c] = src[c];
+    }
+    half_t* dst = y + i * CPAD;
+    if (CPAD == 4) *(half4*)dst = *(half4*)v; else *(half8*)dst = *(half8*)v;
+}
+
+int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, int Hp, int Wp, int Cpad,
+                      int pad_top, int pad_left, int hp, hipStream_t stream) {
+    if (!x || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C > Cpad || (Cpad != 4 && Cpad != 8) ||
+        Hp < H + pad_top || Wp < W + pad_left) { set_error("pack: invalid shape"); return -5; }
+    const long long total = (long long)N * Hp * Wp;
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) { set_error("pack: grid too large"); return -5; }
+    if (Cpad == 4)
+        hipLaunchKernelGGL(pack_input_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, y, Hp, Wp, pad_top, pad_left, hp);
+    else
+        hipLaunchKernelGGL(pack_input_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, y, Hp, Wp, pad_top, pad_left, hp);
+    STRAIT_CHECK_LAUNCH("pack");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// depthwise 3x3, pad 1, stride 1 or 2, fused bias + activation.
+// A thread owns 8 channels (16 bytes) of TW consecutive output pixels of one output row and
+// slides the 3-column window along it, so every input vector is loaded once per thread; lanes of
+// a wavefront cover consecutive channel groups, i.e. contiguous memory.
+template <int STRIDE, int TW>
+__global__ void __launch_bounds__(256) dwconv3x3_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
+                                                         const half_t* __restrict__ w, const float* __restrict__ bias,
+                                                         int act, half_t* __restrict__ y, int P, int Q, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int C8 = C >> 3;
+    const int QT = (Q + TW - 1) / TW;
+    const long long total = (long long)N * P * QT * C8;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c8 = (int)(i % C8);
+    long long t = i / C8;
+    const int qt = (int)(t % QT); t /= QT;
+    const int pp = (int)(t % P);
+    const int n = (int)(t / P);
+    const int c = c8 * 8;
+
+    float wv[9][8];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) {
+        const half8 h = *(const half8*)(w + (long long)k * C + c);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wv[k][j] = (float)h[j];
+    }
+    float bv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) bv[j] = bias ? bias[c + j] : 0.f;
+
+    const int q0 = qt * TW;
+    const int ih0 = pp * STRIDE - 1;
+#pragma unroll
+    for (int tq = 0; tq < TW; ++tq) {
+        const int q = q0 + tq;
+        if (q >= Q) break;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = bv[j];
+        const int iw0 = q * STRIDE - 1;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = ih0 + r;
+            if ((unsigned)ih >= (unsigned)H) continue;
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int iw = iw0 + s;
+                if ((unsigned)iw >= (unsigned)W) continue;
+                const half8 xv = *(const half8*)(x + (((long long)n * H + ih) * W + iw) * C + c);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += (float)xv[j] * wv[r * 3 + s][j];
+            }
+        }
+        half8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (half_t)act_f(acc[j], act);
+        *(half8*)(y + (((long long)n * P + pp) * Q + q) * C + c) = o;
+    }
+}
+
+int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
+                     int stride, int act, half_t* y, int hp, hipStream_t stream) {
+    if (!x || !w_rsc || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || (stride != 1 && stride != 2)) {
+        set_error("dwconv3x3: needs C %% 8 == 0 and stride 1 or 2"); return -5;
+    }
+    const int P = (H + 2 - 3) / stride + 1, Q = (W + 2 - 3) / stride + 1;
+    constexpr int TW = 2;
+    const long long total = (long long)N * P * ((Q + TW - 1) / TW) * (C / 8);
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) { set_error("dwconv3x3: grid too large"); return -5; }
+    if (stride == 1)
+        hipLaunchKernelGGL((dwconv3x3_kernel<1, TW>), dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, P, Q, hp);
+    else
+        hipLaunchKernelGGL((dwconv3x3_kernel<2, TW>), dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, P, Q, hp);
+    STRAIT_CHECK_LAUNCH("dwconv3x3");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// max pooling 3x3 / stride 2 / pad 1.  Thread = 8 channels of one output pixel.
+__global__ void __launch_bounds__(256) maxpool3x3s2_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
+                                                            half_t* __restrict__ y, int P, int Q, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int C8 = C >> 3;
+    const long long total = (long long)N * P * Q * C8;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c8 = (int)(i % C8);
+    long long t = i / C8;
+    const int q = (int)(t % Q); t /= Q;
+    const int pp = (int)(t % P);
+    const int n = (int)(t / P);
+    half8 m;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m[j] = (half_t)(-65504.f);
+    bool any = false;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int ih = pp * 2 - 1 + r;
+        if ((unsigned)ih >= (unsigned)H) continue;
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int iw = q * 2 - 1 + s;
+            if ((unsigned)iw >= (unsigned)W) continue;
+            const half8 v = *(const half8*)(x + (((long long)n * H + ih) * W + iw) * C + c8 * 8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m[j] = (!any || v[j] > m[j]) ? v[j] : m[j];
+            any = true;
+        }
+    }
+    *(half8*)(y + (((long long)n * P + pp) * Q + q) * C + c8 * 8) = m;
+}
+
+int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream) {
+    if (!x || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0) { set_error("maxpool: needs C %% 8 == 0"); return -5; }
+    const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+    const long long blocks = ((long long)N * P * Q * (C / 8) + 255) / 256;
+    if (blocks > 0x7fffffffLL) { set_error("maxpool: grid too large"); return -5; }
+    hipLaunchKernelGGL(maxpool3x3s2_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, y, P, Q, hp);
+    STRAIT_CHECK_LAUNCH("maxpool");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// global average pooling: [N][HW][C] -> [N][C], fp32 sum / HW, rounded once to fp16.
+__global__ void __launch_bounds__(256) gap_kernel(const half_t* __restrict__ x, int N, int HW, int C,
+                                                   half_t* __restrict__ y, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int C8 = C >> 3;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long long)N * C8) return;
+    const int c8 = (int)(i % C8), n = (int)(i / C8);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const half_t* src = x + (long long)n * HW * C + c8 * 8;
+    for (int k = 0; k < HW; ++k) {
+        const half8 v = *(const half8*)(src + (long long)k * C);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (float)v[j];
+    }
+    const float inv = 1.f / (float)HW;
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (half_t)(acc[j] * inv);
+    *(half8*)(y + (long long)n * C + c8 * 8) = o;
+}
+
+int launch_global_avgpool(const half_t* x, int N, int HW, int C, half_t* y, int hp, hipStream_t stream) {
+    if (!x || !y || N <= 0 || HW <= 0 || C <= 0 || C % 8 != 0) { set_error("avgpool: needs C %% 8 == 0"); return -5; }
+    const long long blocks = ((long long)N * (C / 8) + 255) / 256;
+    hipLaunchKernelGGL(gap_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, HW, C, y, hp);
+    STRAIT_CHECK_LAUNCH("avgpool");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// wavefront reductions (64 lanes) through cross-lane shuffles
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// softmax + top-1: one wavefront per row of fp32 logits.
+__global__ void __launch_bounds__(256) softmax_top1_kernel(const float* __restrict__ logits, int rows, int n,
+                                                            float* __restrict__ probs, int32_t* __restrict__ top1, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* src = logits + (long long)row * n;
+    float mx = -INFINITY;
+    int mi = 0x7fffffff;
+    for (int i = lane; i < n; i += 64) {
+        const float v = src[i];
+        if (v > mx) { mx = v; mi = i; }       // ascending i: keeps the lowest index on ties
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(mx, o, 64);
+        const int oi = __shfl_xor(mi, o, 64);
+        if (ov > mx || (ov == mx && oi < mi)) { mx = ov; mi = oi; }
+    }
+    float sum = 0.f;
+    for (int i = lane; i < n; i += 64) sum += __expf(src[i] - mx);
+    sum = wave_sum(sum);
+    const float inv = 1.f / sum;
+    float* dst = probs + (long long)row * n;
+    for (int i = lane; i < n; i += 64) dst[i] = __expf(src[i] - mx) * inv;
+    if (lane == 0) top1[row] = mi;
+}
+
+int launch_softmax_top1(const float* logits, int rows, int n, float* probs, int32_t* top1, int hp, hipStream_t stream) {
+    if (!logits || !probs || !top1 || rows <= 0 || n <= 0) { set_error("softmax: invalid shape"); return -5; }
+    hipLaunchKernelGGL(softmax_top1_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, logits, rows, n, probs, top1, hp);
+    STRAIT_CHECK_LAUNCH("softmax");
+    return 0;
+}
+
+// argmax over n fp16 features of selected rows: one wavefront per row.
+__global__ void __launch_bounds__(256) argmax_f16_kernel(const half_t* __restrict__ x, int rows, int n, long long row_stride,
+                                                          int32_t* __restrict__ top1, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const half_t* src = x + (long long)row * row_stride;
+    float mx = -INFINITY;
+    int mi = 0x7fffffff;
+    for (int i = lane; i < n; i += 64) {
+        const float v = (float)src[i];
+        if (v > mx) { mx = v; mi = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(mx, o, 64);
+        const int oi = __shfl_xor(mi, o, 64);
+        if (ov > mx || (ov == mx && oi < mi)) { mx = ov; mi = oi; }
+    }
+    if (lane == 0) top1[row] = mi;
+}
+
+int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, int32_t* top1, int hp, hipStream_t stream) {
+    if (!x || !top1 || rows <= 0 || n <= 0 || row_stride < n) { set_error("argmax: invalid shape"); return -5; }
+    hipLaunchKernelGGL(argmax_f16_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, x, rows, n, row_stride, top1, hp);
+    STRAIT_CHECK_LAUNCH("argmax");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm: one wavefront per row, the row held in registers (n <= 8192 -> at most 16 chunks
+// of 8 per lane), two-pass mean / variance in fp32.
+template <int MAXC>
+__global__ void __launch_bounds__(256) layernorm_kernel(const half_t* __restrict__ x, const float* __restrict__ gamma,
+                                                         const float* __restrict__ beta, int rows, int n, float eps,
+                                                         half_t* __restrict__ y, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int nch = n >> 3;
+    const half_t* src = x + (long long)row * n;
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int idx = lane + c * 64;
+        if (idx < nch) {
+            const half8 h = *(const half8*)(src + idx * 8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { v[c][j] = (float)h[j]; s += v[c][j]; }
+        }
+    }
+    const float mean = wave_sum(s) / (float)n;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+        if (lane + c * 64 < nch) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const float d = v[c][j] - mean; q += d * d; }
+        }
+    const float rstd = 1.f / sqrtf(wave_sum(q) / (float)n + eps);
+    half_t* dst = y + (long long)row * n;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int idx = lane + c * 64;
+        if (idx < nch) {
+            half8 o;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                o[j] = (half_t)((v[c][j] - mean) * rstd * gamma[idx * 8 + j] + beta[idx * 8 + j]);
+            *(half8*)(dst + idx * 8) = o;
+        }
+    }
+}
+
+int launch_layernorm(const half_t* x, const float* gamma, const float* beta, int rows, int n, float eps,
+                     half_t* y, int hp, hipStream_t stream) {
+    if (!x || !gamma || !beta || !y || rows <= 0 || n <= 0 || n % 8 != 0 || n > 8192) {
+        set_error("layernorm: needs n %% 8 == 0 and n <= 8192"); return -5;
+    }
+    const dim3 grid((rows + 3) / 4), block(256);
+    const int nch = n / 8;
+    if (nch <= 128)
+        hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+    else if (nch <= 512)
+        hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+    else
+        hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+    STRAIT_CHECK_LAUNCH("layernorm");
+    return 0;
+}
+
+}  // namespace strait

@@ -1,0 +1,61 @@
+// Internal launcher interface between the runtime and the gfx950 kernels.
+// Every launcher validates the operand shapes its kernel and grid assume and returns a
+// negative status (see strait.h) instead of launching when they do not hold.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace strait {
+
+typedef _Float16 half_t;
+
+enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+
+// One implicit-GEMM convolution (or plain GEMM) launch.
+//   y[m, k] = act(bias[k] + sum_{r,s,c} x[addr(m) + r*sH + s*sW + c] * w[k*ldw + (r*S + s)*C + c] (+ res[m*ldy + k]))
+// with m = (n, p, q), addr(m) = n*sN + (p*stride - pad)*sH + (q*stride_w - pad_w)*sW, taps outside
+// [0,H) x [0,W) contributing zero.  A plain NHWC convolution has sW = C, sH = W*C, sN = H*W*C;
+// the decoupled strides also describe a channel-padded, spatially pre-padded stem input whose
+// taps along a row are contiguous ("virtual" 1-wide kernel with C = taps*Cpad).
+struct ConvParams {
+    const half_t* x;
+    const half_t* w;
+    const float* bias;       // [Cout] or nullptr
+    const half_t* res;       // [M][ldy] or nullptr
+    void* y;                 // fp16 (or fp32 when out_f32) [M][ldy]
+    int M;                   // N * P * Q
+    int PQ, Q;
+    int H, W, C, R, S;
+    int stride_h, stride_w, pad_h, pad_w;
+    long long sN;
+    int sH, sW;
+    int Kg;                  // R * S * C
+    int ldw;                 // weight row pitch in elements (multiple of 8, zero padded past Kg)
+    int Cout, ldy;
+    int act;
+    int out_f32;
+    int hp;                  // raise wave priority (high-priority batch)
+};
+
+int launch_conv(const ConvParams& p, hipStream_t stream);
+
+int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, int Hp, int Wp, int Cpad,
+                      int pad_top, int pad_left, int hp, hipStream_t stream);
+int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
+                     int stride, int act, half_t* y, int hp, hipStream_t stream);
+int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream);
+int launch_global_avgpool(const half_t* x, int N, int HW, int C, half_t* y, int hp, hipStream_t stream);
+int launch_softmax_top1(const float* logits, int rows, int n, float* probs, int32_t* top1, int hp,
+                        hipStream_t stream);
+int launch_layernorm(const half_t* x, const float* gamma, const float* beta, int rows, int n, float eps,
+                     half_t* y, int hp, hipStream_t stream);
+int launch_attention(const half_t* qkv, const int32_t* valid_len, int B, int S, int heads, half_t* out, int hp,
+                     hipStream_t stream);
+int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, int32_t* top1, int hp,
+                      hipStream_t stream);
+// Weight preparation on the device (load time): BatchNorm fold + OIHW -> kernel layout.
+int launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+
+void set_error(const char* fmt, ...);
+
+}  // namespace strait

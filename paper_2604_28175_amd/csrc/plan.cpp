@@ -1,0 +1,667 @@
+// Model load (paper Section 3, first paragraph after Figure 3: models are loaded and their
+// instances initialised before serving) and the per-batch kernel sequence (Section 3.2 step (2)).
+//
+// Load: parse the weight container, fold BatchNorm into the preceding convolution in fp32
+// (scale = gamma / sqrt(var + 1e-5); w' = fp16(w * scale); b' = beta - mean * scale), re-lay
+// OIHW weights as [K][R][S][C] to match NHWC activations, upload, and lay out the layer plan.
+// Run: enqueue every layer of the plan on one stream, no host synchronisation in between.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "runtime.hpp"
+
+namespace strait {
+
+static thread_local char g_err[512] = "";
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+const char* last_error() { return g_err; }
+
+#define HIP_TRY(expr)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) { set_error("%s: %s", #expr, hipGetErrorString(e_)); return STRAIT_E_HIP; } \
+    } while (0)
+
+// ------------------------------------------------------------------------------------------
+// container
+struct TensorView { const half_t* data; int ndim; unsigned shape[4]; size_t count; };
+
+struct Container {
+    int arch = 0;
+    unsigned hyper[8] = {0};
+    std::map<std::string, TensorView> t;
+    const TensorView* find(const std::string& name) const {
+        auto it = t.find(name);
+        if (it == t.end()) { set_error("weight container: tensor '%s' missing", name.c_str()); return nullptr; }
+        return &it->second;
+    }
+};
+
+static int parse_container(const void* blob, size_t bytes, Container& c) {
+    const unsigned char* p = (const unsigned char*)blob;
+    if (!p || bytes < 48 || memcmp(p, "STRW", 4) != 0) { set_error("weight container: bad magic"); return STRAIT_E_FORMAT; }
+    unsigned head[11];
+    memcpy(head, p + 4, sizeof(head));
+    if (head[0] != 1) { set_error("weight container: unsupported version %u", head[0]); return STRAIT_E_FORMAT; }
+    c.arch = (int)head[1];
+    const unsigned n = head[2];
+    memcpy(c.hyper, head + 3, 32);
+    if ((size_t)48 + (size_t)n * 80 > bytes) { set_error("weight container: truncated table"); return STRAIT_E_FORMAT; }
+    for (unsigned i = 0; i < n; ++i) {
+        const unsigned char* e = p + 48 + (size_t)i * 80;
+        char name[41];
+        memcpy(name, e, 40);
+        name[40] = 0;
+        unsigned meta[6];
+        memcpy(meta, e + 40, 24);
+        unsigned long long off, nb;
+        memcpy(&off, e + 64, 8);
+        memcpy(&nb, e + 72, 8);
+        TensorView v;
+        v.ndim = (int)meta[1];
+        if (meta[0] != 0 || v.ndim < 1 || v.ndim > 4) { set_error("weight container: tensor '%s' has unsupported dtype/rank", name); return STRAIT_E_FORMAT; }
+        v.count = 1;
+        for (int d = 0; d < 4; ++d) { v.shape[d] = meta[2 + d]; if (d < v.ndim) v.count *= v.shape[d]; }
+        if (nb != v.count * 2 || off % 2 != 0 || off > bytes || nb > bytes - off) { set_error("weight container: tensor '%s' out of bounds", name); return STRAIT_E_FORMAT; }
+        v.data = (const half_t*)(p + off);
+        c.t[name] = v;
+    }
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// weight preparation (host) + upload
+struct Loader {
+    Model& m;
+    const Container& c;
+    int upload(const void* host, size_t bytes, void** dev) {
+        void* d = nullptr;
+        const size_t padded = (bytes + 255) / 256 * 256;
+        if (hipMalloc(&d, padded) != hipSuccess) { set_error("hipMalloc(%zu) for weights failed", padded); return STRAIT_E_NOMEM; }
+        m.dev_allocs.push_back(d);
+        HIP_TRY(hipMemset(d, 0, padded));
+        HIP_TRY(hipMemcpy(d, host, bytes, hipMemcpyHostToDevice));
+        *dev = d;
+        return 0;
+    }
+    static bool shape_is(const TensorView* v, std::initializer_list<unsigned> s) {
+        if (!v || v->ndim != (int)s.size()) return false;
+        int i = 0;
+        for (unsigned d : s) if (v->shape[i++] != d) return false;
+        return true;
+    }
+    // per-output-channel scale and bias: BatchNorm fold, or plain bias tensor, in fp32
+    int scale_bias(const std::string& name, bool bn, unsigned K, std::vector<float>& scale, std::vector<float>& bias) {
+        scale.assign(K, 1.f);
+        bias.assign(K, 0.f);
+        if (bn) {
+            const TensorView *g = c.find(name + ".gamma"), *b = c.find(name + ".beta"), *mu = c.find(name + ".mean"), *var = c.find(name + ".var");
+            if (!g || !b || !mu || !var) return STRAIT_E_FORMAT;
+            if (!shape_is(g, {K}) || !shape_is(b, {K}) || !shape_is(mu, {K}) || !shape_is(var, {K})) { set_error("'%s': BatchNorm vectors must have %u entries", name.c_str(), K); return STRAIT_E_FORMAT; }
+            for (unsigned k = 0; k < K; ++k) {
+                const float s = (float)g->data[k] / sqrtf((float)var->data[k] + 1e-5f);
+                volatile float ms = (float)mu->data[k] * s;       // two roundings: no fused multiply-add
+                scale[k] = s;
+                bias[k] = (float)b->data[k] - ms;
+            }
+        } else {
+            const TensorView* b = c.find(name + ".b");
+            if (!b) return STRAIT_E_FORMAT;
+            if (!shape_is(b, {K})) { set_error("'%s.b': expected %u entries", name.c_str(), K); return STRAIT_E_FORMAT; }
+            for (unsigned k = 0; k < K; ++k) bias[k] = (float)b->data[k];
+        }
+        return 0;
+    }
+    // OIHW [K][C][R][S] -> [K][R][S][C] with the fold scale applied, row pitch ldw (>= R*S*C, zero padded)
+    int conv_weights(const std::string& name, bool bn, unsigned K, unsigned C, unsigned R, unsigned S, Op& op) {
+        const TensorView* w = c.find(name + ".w");
+        if (!w) return STRAIT_E_FORMAT;
+        if (!shape_is(w, {K, C, R, S})) { set_error("'%s.w': expected [%u,%u,%u,%u]", name.c_str(), K, C, R, S); return STRAIT_E_FORMAT; }
+        std::vector<float> scale, bias;
+        int rc = scale_bias(name, bn, K, scale, bias);
+        if (rc) return rc;
+        const unsigned Kg = R * S * C, ldw = (Kg + 7) / 8 * 8;
+        std::vector<half_t> out((size_t)K * ldw, (half_t)0);
+        for (unsigned k = 0; k < K; ++k)
+            for (unsigned cc = 0; cc < C; ++cc)
+                for (unsigned r = 0; r < R; ++r)
+                    for (unsigned s = 0; s < S; ++s) {
+                        const float v = (float)w->data[((k * C + cc) * R + r) * S + s];
+                        out[(size_t)k * ldw + (r * S + s) * C + cc] = bn ? (half_t)(v * scale[k]) : (half_t)v;
+                    }
+        void *dw = nullptr, *db = nullptr;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bias.data(), bias.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.ldw = (int)ldw;
+        op.info.weight_bytes = (int64_t)K * Kg * 2 + K * 4;
+        return 0;
+    }
+    // Stem: OIHW [K][C][R][S] -> [K][R][Sv*Cpad] with taps s >= S and channels c >= C zero.
+    int stem_weights(const std::string& name, bool bn, unsigned K, unsigned C, unsigned R, unsigned S, unsigned Sv, unsigned Cpad, Op& op) {
+        const TensorView* w = c.find(name + ".w");
+        if (!w) return STRAIT_E_FORMAT;
+        if (!shape_is(w, {K, C, R, S})) { set_error("'%s.w': expected [%u,%u,%u,%u]", name.c_str(), K, C, R, S); return STRAIT_E_FORMAT; }
+        std::vector<float> scale, bias;
+        int rc = scale_bias(name, bn, K, scale, bias);
+        if (rc) return rc;
+        const unsigned Cv = Sv * Cpad, ldw = R * Cv;
+        std::vector<half_t> out((size_t)K * ldw, (half_t)0);
+        for (unsigned k = 0; k < K; ++k)
+            for (unsigned cc = 0; cc < C; ++cc)
+                for (unsigned r = 0; r < R; ++r)
+                    for (unsigned s = 0; s < S; ++s) {
+                        const float v = (float)w->data[((k * C + cc) * R + r) * S + s];
+                        out[(size_t)k * ldw + r * Cv + s * Cpad + cc] = bn ? (half_t)(v * scale[k]) : (half_t)v;
+                    }
+        void *dw = nullptr, *db = nullptr;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bias.data(), bias.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.ldw = (int)ldw;
+        op.info.weight_bytes = (int64_t)K * C * R * S * 2 + K * 4;
+        return 0;
+    }
+    // depthwise [C][1][3][3] -> [3][3][C]
+    int dw_weights(const std::string& name, unsigned C, Op& op) {
+        const TensorView* w = c.find(name + ".w");
+        if (!w) return STRAIT_E_FORMAT;
+        if (!shape_is(w, {C, 1, 3, 3})) { set_error("'%s.w': expected [%u,1,3,3]", name.c_str(), C); return STRAIT_E_FORMAT; }
+        std::vector<float> scale, bias;
+        int rc = scale_bias(name, true, C, scale, bias);
+        if (rc) return rc;
+        std::vector<half_t> out((size_t)9 * C);
+        for (unsigned cc = 0; cc < C; ++cc)
+            for (unsigned k = 0; k < 9; ++k) out[(size_t)k * C + cc] = (half_t)((float)w->data[cc * 9 + k] * scale[cc]);
+        void *dw = nullptr, *db = nullptr;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bias.data(), bias.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.info.weight_bytes = (int64_t)C * 9 * 2 + C * 4;
+        return 0;
+    }
+    // linear layers: rows of several [out_i, in] matrices stacked, biases concatenated
+    int linear_weights(std::initializer_list<std::string> names, unsigned in, Op& op, unsigned* total_out) {
+        std::vector<half_t> w;
+        std::vector<float> b;
+        for (const std::string& nm : names) {
+            const TensorView *tw = c.find(nm + ".w"), *tb = c.find(nm + ".b");
+            if (!tw || !tb) return STRAIT_E_FORMAT;
+            if (tw->ndim != 2 || tw->shape[1] != in || !shape_is(tb, {tw->shape[0]})) { set_error("'%s': expected [out,%u] weight and [out] bias", nm.c_str(), in); return STRAIT_E_FORMAT; }
+            w.insert(w.end(), tw->data, tw->data + tw->count);
+            for (unsigned i = 0; i < tb->count; ++i) b.push_back((float)tb->data[i]);
+        }
+        if (in % 8 != 0) { set_error("linear layer input width %u must be a multiple of 8", in); return STRAIT_E_SHAPE; }
+        void *dw = nullptr, *db = nullptr;
+        int rc;
+        if ((rc = upload(w.data(), w.size() * 2, &dw))) return rc;
+        if ((rc = upload(b.data(), b.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.ldw = (int)in;
+        *total_out = (unsigned)b.size();
+        op.info.weight_bytes = (int64_t)w.size() * 2 + (int64_t)b.size() * 4;
+        return 0;
+    }
+    int vector_f32(const std::string& name, unsigned n, const float** dev) {
+        const TensorView* v = c.find(name);
+        if (!v) return STRAIT_E_FORMAT;
+        if (!shape_is(v, {n})) { set_error("'%s': expected %u entries", name.c_str(), n); return STRAIT_E_FORMAT; }
+        std::vector<float> f(n);
+        for (unsigned i = 0; i < n; ++i) f[i] = (float)v->data[i];
+        void* d = nullptr;
+        int rc = upload(f.data(), f.size() * 4, &d);
+        *dev = (const float*)d;
+        return rc;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// activation buffer planning: a handful of reusable buffers, sized per sample
+struct Planner {
+    Model& m;
+    std::vector<bool> busy;
+    int get(size_t elems) {
+        int best = -1;
+        for (size_t i = 0; i < busy.size(); ++i)
+            if (!busy[i] && (best < 0 || m.buf_elems[i] > m.buf_elems[best])) best = (int)i;
+        if (best < 0) { m.buf_elems.push_back(0); busy.push_back(false); best = (int)busy.size() - 1; }
+        busy[best] = true;
+        if (m.buf_elems[best] < elems) m.buf_elems[best] = elems;
+        return best;
+    }
+    void put(int slot) { if (slot >= 0) busy[slot] = false; }
+};
+
+static void name_op(Op& op, const std::string& name, int info_kind) {
+    op.name = name;
+    memset(&op.info, 0, sizeof(op.info));
+    snprintf(op.info.name, sizeof(op.info.name), "%s", name.c_str());
+    op.info.kind = info_kind;
+}
+
+struct Builder {
+    Model& m;
+    Loader& ld;
+    Planner pl;
+
+    static int osz(int h, int k, int stride, int pad) { return (h + 2 * pad - k) / stride + 1; }
+
+    // regular convolution / linear layer on an NHWC activation
+    int conv(const std::string& name, bool bn, int in, int H, int W, int C, int K, int R, int stride, int pad, int act,
+             int res, int out, int* P_out, int* Q_out) {
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = in; op.out = out; op.res = res;
+        op.H = H; op.W = W; op.C = C; op.K = K; op.R = R; op.S = R; op.stride = stride; op.pad = pad; op.act = act;
+        op.P = osz(H, R, stride, pad); op.Q = osz(W, R, stride, pad);
+        op.vC = C; op.vR = R; op.vS = R; op.vH = H; op.vW = W;
+        op.sN = (long long)H * W * C; op.sH = W * C; op.sW = C; op.stride_w = stride; op.pad_h = pad; op.pad_w = pad;
+        int rc = ld.conv_weights(name, bn, K, C, R, R, op);
+        if (rc) return rc;
+        op.info.macs_per_sample = (int64_t)op.P * op.Q * K * R * R * C;
+        op.info.bytes_per_sample = 2LL * ((int64_t)H * W * C + (int64_t)op.P * op.Q * K * (res != SLOT_NONE ? 2 : 1));
+        op.info.gemm_m_per_sample = op.P * op.Q; op.info.gemm_n = K; op.info.gemm_k = R * R * C;
+        if (P_out) *P_out = op.P;
+        if (Q_out) *Q_out = op.Q;
+        m.ops.push_back(op);
+        return 0;
+    }
+
+    // 3-channel stem: pack to a zero-bordered, channel-padded image, then a convolution whose
+    // row taps are contiguous in memory
+    int stem(const std::string& name, bool bn, int H, int W, int C, int K, int R, int stride, int pad, int act, int out_slot_elems_hint,
+             int* out_slot, int* P_out, int* Q_out) {
+        (void)out_slot_elems_hint;
+        const int Cpad = (stride * 4) % 8 == 0 ? 4 : 8;
+        int Sv = R;
+        while ((Sv * Cpad) % 8 != 0) ++Sv;
+        const int P = osz(H, R, stride, pad), Q = osz(W, R, stride, pad);
+        int Hp = std::max(H + 2 * pad, (P - 1) * stride + R);
+        int Wp = std::max(W + 2 * pad, (Q - 1) * stride + Sv);
+        while ((Wp * Cpad) % 8 != 0) ++Wp;
+        const int pk = pl.get((size_t)Hp * Wp * Cpad);
+        Op pack;
+        name_op(pack, name + ".pack", 6);
+        pack.kind = OP_PACK;
+        pack.in = SLOT_INPUT; pack.out = pk;
+        pack.H = H; pack.W = W; pack.C = C; pack.Hp = Hp; pack.Wp = Wp; pack.Cpad = Cpad; pack.pad = pad;
+        pack.P = Hp; pack.Q = Wp; pack.K = Cpad;
+        pack.info.bytes_per_sample = 2LL * ((int64_t)H * W * C + (int64_t)Hp * Wp * Cpad);
+        m.ops.push_back(pack);
+
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = pk; op.res = SLOT_NONE;
+        op.H = H; op.W = W; op.C = C; op.K = K; op.R = R; op.S = R; op.stride = stride; op.pad = pad; op.act = act;
+        op.P = P; op.Q = Q;
+        op.vC = Sv * Cpad; op.vR = R; op.vS = 1; op.vH = Hp; op.vW = Q;
+        op.sN = (long long)Hp * Wp * Cpad; op.sH = Wp * Cpad; op.sW = stride * Cpad; op.stride_w = 1; op.pad_h = 0; op.pad_w = 0;
+        int rc = ld.stem_weights(name, bn, K, C, R, R, Sv, Cpad, op);
+        if (rc) return rc;
+        op.out = pl.get((size_t)P * Q * K);
+        pl.put(pk);
+        op.info.macs_per_sample = (int64_t)P * Q * K * R * R * C;
+        op.info.bytes_per_sample = 2LL * ((int64_t)Hp * Wp * Cpad + (int64_t)P * Q * K);
+        op.info.gemm_m_per_sample = P * Q; op.info.gemm_n = K; op.info.gemm_k = R * op.vC;
+        m.ops.push_back(op);
+        *out_slot = op.out; *P_out = P; *Q_out = Q;
+        return 0;
+    }
+
+    int dwconv(const std::string& name, int in, int H, int W, int C, int stride, int out, int* P_out, int* Q_out) {
+        Op op;
+        name_op(op, name, 1);
+        op.kind = OP_DWCONV;
+        op.in = in; op.out = out;
+        op.H = H; op.W = W; op.C = C; op.K = C; op.R = op.S = 3; op.stride = stride; op.pad = 1; op.act = ACT_RELU6;
+        op.P = osz(H, 3, stride, 1); op.Q = osz(W, 3, stride, 1);
+        int rc = ld.dw_weights(name, C, op);
+        if (rc) return rc;
+        op.info.macs_per_sample = (int64_t)op.P * op.Q * C * 9;
+        op.info.bytes_per_sample = 2LL * ((int64_t)H * W * C + (int64_t)op.P * op.Q * C);
+        *P_out = op.P; *Q_out = op.Q;
+        m.ops.push_back(op);
+        return 0;
+    }
+
+    void pool(const std::string& name, int sub, int in, int H, int W, int C, int out, int out_ref = 0) {
+        Op op;
+        name_op(op, name, 2);
+        op.kind = OP_POOL; op.sub = sub;
+        op.in = in; op.out = out; op.out_ref = out_ref;
+        op.H = H; op.W = W; op.C = C; op.K = C;
+        if (sub == POOL_MAX3X3S2) { op.P = osz(H, 3, 2, 1); op.Q = osz(W, 3, 2, 1); }
+        op.info.bytes_per_sample = 2LL * ((int64_t)H * W * C + (int64_t)op.P * op.Q * C);
+        m.ops.push_back(op);
+    }
+
+    // GAP -> FC (fp32 logits into the output buffer) -> softmax + top-1
+    int classifier(int feat_in, int HW_h, int HW_w, int C, int classes) {
+        const int f = pl.get(C);
+        pool("gap", POOL_GLOBAL_AVG, feat_in, HW_h, HW_w, C, f);
+        pl.put(feat_in);
+        Op fc;
+        name_op(fc, "fc", 0);
+        fc.kind = OP_CONV;
+        fc.in = f; fc.out = SLOT_OUT; fc.out_ref = 0; fc.out_f32 = 1;
+        fc.C = C; fc.K = classes; fc.vC = C; fc.vR = fc.vS = 1; fc.vH = fc.vW = 1;
+        fc.sN = C; fc.sH = C; fc.sW = C;
+        unsigned nout = 0;
+        int rc = ld.linear_weights({"fc"}, C, fc, &nout);
+        if (rc) return rc;
+        if ((int)nout != classes) { set_error("fc: expected %d outputs, container has %u", classes, nout); return STRAIT_E_FORMAT; }
+        fc.info.macs_per_sample = (int64_t)C * classes;
+        fc.info.bytes_per_sample = 2LL * C + 4LL * classes;
+        fc.info.gemm_m_per_sample = 1; fc.info.gemm_n = classes; fc.info.gemm_k = C;
+        m.ops.push_back(fc);
+        pl.put(f);
+        Op sm;
+        name_op(sm, "softmax", 3);
+        sm.kind = OP_SOFTMAX;
+        sm.in = SLOT_OUT; sm.out = SLOT_OUT; sm.out_ref = 1; sm.out_ref2 = 2; sm.K = classes;
+        sm.info.bytes_per_sample = 8LL * classes + 4;
+        m.ops.push_back(sm);
+        return 0;
+    }
+};
+
+static int plan_tiny_cnn(Model& m, Builder& b) {
+    const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3];
+    int cur, P, Q, rc;
+    if ((rc = b.stem("conv0", false, H, W, C, 16, 3, 1, 1, ACT_RELU, 0, &cur, &P, &Q))) return rc;
+    int cin = 16;
+    const int couts[2] = {32, 64};
+    for (int i = 0; i < 2; ++i) {
+        const int o = b.pl.get((size_t)b.osz(P, 3, 2, 1) * b.osz(Q, 3, 2, 1) * couts[i]);
+        char nm[16];
+        snprintf(nm, sizeof(nm), "conv%d", i + 1);
+        if ((rc = b.conv(nm, false, cur, P, Q, cin, couts[i], 3, 2, 1, ACT_RELU, SLOT_NONE, o, &P, &Q))) return rc;
+        b.pl.put(cur);
+        cur = o; cin = couts[i];
+    }
+    return b.classifier(cur, P, Q, cin, classes);
+}
+
+static int plan_resnet50(Model& m, Builder& b) {
+    const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3];
+    int cur, P, Q, rc;
+    if ((rc = b.stem("stem", true, H, W, C, 64, 7, 2, 3, ACT_RELU, 0, &cur, &P, &Q))) return rc;
+    {
+        const int P2 = b.osz(P, 3, 2, 1), Q2 = b.osz(Q, 3, 2, 1);
+        const int o = b.pl.get((size_t)P2 * Q2 * 64);
+        b.pool("maxpool", POOL_MAX3X3S2, cur, P, Q, 64, o);
+        b.pl.put(cur);
+        cur = o; P = P2; Q = Q2;
+    }
+    int cin = 64;
+    const int nblocks[4] = {3, 4, 6, 3}, planes[4] = {64, 128, 256, 512};
+    for (int si = 0; si < 4; ++si)
+        for (int bi = 0; bi < nblocks[si]; ++bi) {
+            char pre[16];
+            snprintf(pre, sizeof(pre), "s%db%d", si + 1, bi);
+            const std::string p(pre);
+            const int pln = planes[si], stride = (bi == 0 && si > 0) ? 2 : 1;
+            const int P2 = b.osz(P, 3, stride, 1), Q2 = b.osz(Q, 3, stride, 1);
+            const int t1 = b.pl.get((size_t)P * Q * pln);
+            if ((rc = b.conv(p + ".c1", true, cur, P, Q, cin, pln, 1, 1, 0, ACT_RELU, SLOT_NONE, t1, nullptr, nullptr))) return rc;
+            const int t2 = b.pl.get((size_t)P2 * Q2 * pln);
+            if ((rc = b.conv(p + ".c2", true, t1, P, Q, pln, pln, 3, stride, 1, ACT_RELU, SLOT_NONE, t2, nullptr, nullptr))) return rc;
+            b.pl.put(t1);
+            int sc = cur;
+            if (bi == 0) {
+                sc = b.pl.get((size_t)P2 * Q2 * pln * 4);
+                if ((rc = b.conv(p + ".down", true, cur, P, Q, cin, pln * 4, 1, stride, 0, ACT_NONE, SLOT_NONE, sc, nullptr, nullptr))) return rc;
+                b.pl.put(cur);
+            }
+            const int o = b.pl.get((size_t)P2 * Q2 * pln * 4);
+            if ((rc = b.conv(p + ".c3", true, t2, P2, Q2, pln, pln * 4, 1, 1, 0, ACT_RELU, sc, o, nullptr, nullptr))) return rc;
+            b.pl.put(t2);
+            b.pl.put(sc);
+            cur = o; cin = pln * 4; P = P2; Q = Q2;
+        }
+    return b.classifier(cur, P, Q, cin, classes);
+}
+
+static int plan_mobilenet_v2(Model& m, Builder& b) {
+    const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3];
+    int cur, P, Q, rc;
+    if ((rc = b.stem("stem", true, H, W, C, 32, 3, 2, 1, ACT_RELU6, 0, &cur, &P, &Q))) return rc;
+    static const int cfg[7][4] = {{1, 16, 1, 1}, {6, 24, 2, 2}, {6, 32, 3, 2}, {6, 64, 4, 2}, {6, 96, 3, 1}, {6, 160, 3, 2}, {6, 320, 1, 1}};
+    int cin = 32, idx = 0;
+    for (int g = 0; g < 7; ++g)
+        for (int i = 0; i < cfg[g][2]; ++i, ++idx) {
+            const int t = cfg[g][0], cout = cfg[g][1], stride = i == 0 ? cfg[g][3] : 1;
+            const int hid = cin * t;
+            char pre[16];
+            snprintf(pre, sizeof(pre), "b%d", idx);
+            const std::string p(pre);
+            int a = cur;
+            if (t != 1) {
+                a = b.pl.get((size_t)P * Q * hid);
+                if ((rc = b.conv(p + ".expand", true, cur, P, Q, cin, hid, 1, 1, 0, ACT_RELU6, SLOT_NONE, a, nullptr, nullptr))) return rc;
+            }
+            const int P2 = b.osz(P, 3, stride, 1), Q2 = b.osz(Q, 3, stride, 1);
+            const int d = b.pl.get((size_t)P2 * Q2 * hid);
+            int Pd, Qd;
+            if ((rc = b.dwconv(p + ".dw", a, P, Q, hid, stride, d, &Pd, &Qd))) return rc;
+            if (a != cur) b.pl.put(a);
+            const bool residual = stride == 1 && cin == cout;
+            const int o = b.pl.get((size_t)P2 * Q2 * cout);
+            if ((rc = b.conv(p + ".project", true, d, P2, Q2, hid, cout, 1, 1, 0, ACT_NONE, residual ? cur : SLOT_NONE, o, nullptr, nullptr))) return rc;
+            b.pl.put(d);
+            b.pl.put(cur);
+            cur = o; cin = cout; P = P2; Q = Q2;
+        }
+    const int hd = b.pl.get((size_t)P * Q * 1280);
+    if ((rc = b.conv("head", true, cur, P, Q, cin, 1280, 1, 1, 0, ACT_RELU6, SLOT_NONE, hd, nullptr, nullptr))) return rc;
+    b.pl.put(cur);
+    return b.classifier(hd, P, Q, 1280, classes);
+}
+
+static int plan_encoder(Model& m, Builder& b) {
+    const int layers = m.hyper[0], hidden = m.hyper[1], heads = m.hyper[2], ffn = m.hyper[3], seq = m.hyper[4];
+    if (heads <= 0 || hidden != heads * 64) { set_error("encoder: head dimension must be 64 (hidden %d, heads %d)", hidden, heads); return STRAIT_E_SHAPE; }
+    if (seq <= 0 || seq > 128 || seq % 32 != 0) { set_error("encoder: sequence length %d must be a multiple of 32, at most 128", seq); return STRAIT_E_SHAPE; }
+    if (ffn % 8 != 0) { set_error("encoder: ffn width must be a multiple of 8"); return STRAIT_E_SHAPE; }
+    Loader& ld = b.ld;
+    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) -> int {
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = in; op.out = out; op.res = res; op.act = act;
+        op.P = seq; op.Q = 1; op.H = seq; op.W = 1;            // seq rows per sample
+        op.C = K; op.K = N; op.vC = K; op.vR = op.vS = 1; op.vH = op.vW = 1;
+        op.sN = K; op.sH = K; op.sW = K;
+        unsigned nout = 0;
+        int rc = ld.linear_weights(ws, K, op, &nout);
+        if (rc) return rc;
+        if ((int)nout != N) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), N, nout); return STRAIT_E_FORMAT; }
+        op.info.macs_per_sample = (int64_t)seq * K * N;
+        op.info.bytes_per_sample = 2LL * seq * ((int64_t)K + (int64_t)N * (res != SLOT_NONE ? 2 : 1));
+        op.info.gemm_m_per_sample = seq; op.info.gemm_n = N; op.info.gemm_k = K;
+        m.ops.push_back(op);
+        return 0;
+    };
+    auto lnorm = [&](const std::string& name, int in, int out, int out_ref) -> int {
+        Op op;
+        name_op(op, name, 4);
+        op.kind = OP_LAYERNORM;
+        op.in = in; op.out = out; op.out_ref = out_ref; op.P = seq; op.K = hidden; op.eps = 1e-12f;
+        int rc;
+        if ((rc = ld.vector_f32(name + ".g", hidden, &op.bias))) return rc;
+        if ((rc = ld.vector_f32(name + ".b", hidden, &op.beta))) return rc;
+        op.info.bytes_per_sample = 4LL * seq * hidden;
+        op.info.weight_bytes = 8LL * hidden;
+        m.ops.push_back(op);
+        return 0;
+    };
+    int x = SLOT_INPUT, rc;
+    const size_t tok = (size_t)seq * hidden;
+    for (int i = 0; i < layers; ++i) {
+        char pre[16];
+        snprintf(pre, sizeof(pre), "l%d", i);
+        const std::string p(pre);
+        const int qkv = b.pl.get(3 * tok);
+        if ((rc = gemm(p + ".qkv", {p + ".q", p + ".k", p + ".v"}, x, hidden, 3 * hidden, ACT_NONE, SLOT_NONE, qkv))) return rc;
+        const int att = b.pl.get(tok);
+        {
+            Op op;
+            name_op(op, p + ".attn", 5);
+            op.kind = OP_ATTENTION;
+            op.in = qkv; op.out = att; op.seq = seq; op.heads = heads; op.P = seq; op.K = hidden;
+            op.info.macs_per_sample = 2LL * seq * seq * hidden;
+            op.info.bytes_per_sample = 2LL * seq * hidden * 4;
+            m.ops.push_back(op);
+        }
+        b.pl.put(qkv);
+        const int t = b.pl.get(tok);
+        if ((rc = gemm(p + ".o", {p + ".o"}, att, hidden, hidden, ACT_NONE, x, t))) return rc;
+        b.pl.put(att);
+        const int h = b.pl.get(tok);
+        if ((rc = lnorm(p + ".ln1", t, h, 0))) return rc;
+        b.pl.put(t);
+        b.pl.put(x);
+        const int f = b.pl.get((size_t)seq * ffn);
+        if ((rc = gemm(p + ".ffn1", {p + ".ffn1"}, h, hidden, ffn, ACT_GELU, SLOT_NONE, f))) return rc;
+        const int t2 = b.pl.get(tok);
+        if ((rc = gemm(p + ".ffn2", {p + ".ffn2"}, f, ffn, hidden, ACT_NONE, h, t2))) return rc;
+        b.pl.put(f);
+        const bool last = i == layers - 1;
+        const int y = last ? SLOT_OUT : b.pl.get(tok);
+        if ((rc = lnorm(p + ".ln2", t2, y, 0))) return rc;
+        b.pl.put(t2);
+        b.pl.put(h);
+        x = y;
+    }
+    Op am;
+    name_op(am, "argmax", 2);
+    am.kind = OP_POOL; am.sub = POOL_ARGMAX;
+    am.in = SLOT_OUT; am.out = SLOT_OUT; am.out_ref = 3; am.K = hidden; am.P = seq;
+    am.info.bytes_per_sample = 2LL * hidden + 4;
+    m.ops.push_back(am);
+    return 0;
+}
+
+size_t Model::out_bytes(int b) const {
+    if (arch == STRAIT_ARCH_ENCODER) return (size_t)b * seq * hidden * 2 + (size_t)b * 4;
+    return (size_t)b * classes * 8 + (size_t)b * 4;
+}
+size_t Model::out_offset(int ref, int b) const {
+    switch (ref) {
+        case 1: return (size_t)b * classes * 4;
+        case 2: return (size_t)b * classes * 8;
+        case 3: return (size_t)b * seq * hidden * 2;
+        default: return 0;
+    }
+}
+
+int build_plan(Model& m, const void* blob, size_t bytes) {
+    Container c;
+    int rc = parse_container(blob, bytes, c);
+    if (rc) return rc;
+    m.arch = c.arch;
+    for (int i = 0; i < 8; ++i) m.hyper[i] = (int)c.hyper[i];
+    Loader ld{m, c};
+    Builder b{m, ld, Planner{m, {}}};
+    switch (m.arch) {
+        case STRAIT_ARCH_TINY_CNN:
+        case STRAIT_ARCH_RESNET50:
+        case STRAIT_ARCH_MOBILENETV2:
+            if (m.hyper[0] <= 0 || m.hyper[1] <= 0 || m.hyper[2] <= 0 || m.hyper[2] > 4 || m.hyper[3] <= 0 || m.hyper[0] > 4096 || m.hyper[1] > 4096) {
+                set_error("CNN hyper-parameters out of range (H %d, W %d, C %d, classes %d)", m.hyper[0], m.hyper[1], m.hyper[2], m.hyper[3]);
+                return STRAIT_E_SHAPE;
+            }
+            m.in_elems = (size_t)m.hyper[0] * m.hyper[1] * m.hyper[2];
+            m.classes = m.hyper[3];
+            rc = m.arch == STRAIT_ARCH_TINY_CNN ? plan_tiny_cnn(m, b) : m.arch == STRAIT_ARCH_RESNET50 ? plan_resnet50(m, b) : plan_mobilenet_v2(m, b);
+            break;
+        case STRAIT_ARCH_ENCODER:
+            if (m.hyper[0] <= 0 || m.hyper[1] <= 0 || m.hyper[3] <= 0) { set_error("encoder hyper-parameters out of range"); return STRAIT_E_SHAPE; }
+            m.seq = m.hyper[4]; m.hidden = m.hyper[1];
+            m.in_elems = (size_t)m.seq * m.hidden;
+            rc = plan_encoder(m, b);
+            break;
+        default:
+            set_error("unknown architecture id %d", m.arch);
+            return STRAIT_E_FORMAT;
+    }
+    return rc;
+}
+
+// ------------------------------------------------------------------------------------------
+static void* slot_ptr(Model& m, Instance& in, int slot, int ref, int batch) {
+    if (slot == SLOT_INPUT) return in.dev_in;
+    if (slot == SLOT_OUT) return (char*)in.dev_out + m.out_offset(ref, batch);
+    if (slot >= 0) return in.bufs[slot];
+    return nullptr;
+}
+
+int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed) {
+    const int n = (int)m.ops.size();
+    if (last_layer < 0 || last_layer >= n) last_layer = n - 1;
+    for (int i = 0; i <= last_layer; ++i) {
+        const Op& op = m.ops[i];
+        if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
+        const void* src = slot_ptr(m, in, op.in, 0, batch);
+        void* dst = slot_ptr(m, in, op.out, op.out_ref, batch);
+        int rc = 0;
+        switch (op.kind) {
+            case OP_CONV: {
+                ConvParams p{};
+                p.x = (const half_t*)src; p.w = op.w; p.bias = op.bias;
+                p.res = (const half_t*)slot_ptr(m, in, op.res, 0, batch);
+                p.y = dst;
+                p.M = batch * op.P * op.Q; p.PQ = op.P * op.Q; p.Q = op.Q;
+                p.H = op.vH; p.W = op.vW; p.C = op.vC; p.R = op.vR; p.S = op.vS;
+                p.stride_h = op.stride; p.stride_w = op.stride_w; p.pad_h = op.pad_h; p.pad_w = op.pad_w;
+                p.sN = op.sN; p.sH = op.sH; p.sW = op.sW;
+                p.Kg = op.vR * op.vS * op.vC; p.ldw = op.ldw;
+                p.Cout = op.K; p.ldy = op.K; p.act = op.act; p.out_f32 = op.out_f32; p.hp = hp;
+                rc = launch_conv(p, stream);
+                break;
+            }
+            case OP_PACK:
+                rc = launch_pack_input((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, op.Hp, op.Wp, op.Cpad, op.pad, op.pad, hp, stream);
+                break;
+            case OP_DWCONV:
+                rc = launch_dwconv3x3((const half_t*)src, batch, op.H, op.W, op.C, op.w, op.bias, op.stride, op.act, (half_t*)dst, hp, stream);
+                break;
+            case OP_POOL:
+                if (op.sub == POOL_MAX3X3S2) rc = launch_maxpool3x3s2((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, hp, stream);
+                else if (op.sub == POOL_GLOBAL_AVG) rc = launch_global_avgpool((const half_t*)src, batch, op.H * op.W, op.C, (half_t*)dst, hp, stream);
+                else rc = launch_argmax_f16((const half_t*)src, batch, op.K, (long long)op.P * op.K, (int32_t*)dst, hp, stream);
+                break;
+            case OP_SOFTMAX:
+                rc = launch_softmax_top1((const float*)src, batch, op.K, (float*)dst, (int32_t*)slot_ptr(m, in, SLOT_OUT, op.out_ref2, batch), hp, stream);
+                break;
+            case OP_LAYERNORM:
+                rc = launch_layernorm((const half_t*)src, op.bias, op.beta, batch * op.P, op.K, op.eps, (half_t*)dst, hp, stream);
+                break;
+            case OP_ATTENTION:
+                rc = launch_attention((const half_t*)src, in.dev_valid, batch, op.seq, op.heads, (half_t*)dst, hp, stream);
+                break;
+            default:
+                set_error("unknown op kind %d", op.kind);
+                rc = STRAIT_E_INVALID;
+        }
+        if (rc) return rc;
+    }
+    if (timed) HIP_TRY(hipEventRecord(in.layer_ev[last_layer + 1], stream));
+    return 0;
+}
+
+}  // namespace strait

@@ -1,0 +1,119 @@
+// Host-side runtime: weight container, BatchNorm fold and re-layout, per-architecture layer
+// plans, model instances with pinned staging, dual-priority dispatch and completion records.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <condition_variable>
+#include <deque>
+#include <map>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/strait.h"
+#include "kernels.hpp"
+
+namespace strait {
+
+enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_POOL = 2, OP_SOFTMAX = 3, OP_LAYERNORM = 4, OP_ATTENTION = 5, OP_PACK = 6 };
+enum PoolKind { POOL_MAX3X3S2 = 0, POOL_GLOBAL_AVG = 1, POOL_ARGMAX = 2 };
+
+// Where an operand lives.  Slots >= 0 index the instance's activation buffers; the input and
+// output slots are the instance's device input / output buffers (output at a byte offset that
+// depends on the batch size).
+enum { SLOT_NONE = -1, SLOT_INPUT = -2, SLOT_OUT = -3 };
+
+struct OutRef { int kind = 0; };   // 0: start of output buffer, 1: after logits (probs), 2: after logits+probs (top1), 3: after hidden states
+
+struct Op {
+    std::string name;
+    int kind = OP_CONV;
+    int sub = 0;                      // PoolKind for OP_POOL
+    int in = SLOT_NONE, out = SLOT_NONE, res = SLOT_NONE;
+    int out_ref = 0, out_ref2 = 0;    // which region of the output buffer (when out == SLOT_OUT)
+    // geometry per sample
+    int H = 1, W = 1, C = 1;          // input
+    int P = 1, Q = 1, K = 1;          // output
+    int R = 1, S = 1, stride = 1, pad = 0, act = 0;
+    int out_f32 = 0;
+    // implicit-GEMM addressing (elements), see ConvParams
+    long long sN = 0; int sH = 0, sW = 0, stride_w = 1, pad_h = 0, pad_w = 0, vC = 0, vR = 0, vS = 0, vH = 0, vW = 0;
+    int ldw = 0;
+    // pack
+    int Hp = 0, Wp = 0, Cpad = 0;
+    // attention / layernorm
+    int seq = 0, heads = 0;
+    float eps = 0.f;
+    const half_t* w = nullptr;
+    const float* bias = nullptr;      // conv/gemm bias, LayerNorm gamma
+    const float* beta = nullptr;      // LayerNorm beta
+    strait_layer_info info{};
+};
+
+struct Instance {
+    void* pinned_in = nullptr;
+    void* pinned_out = nullptr;
+    void* dev_in = nullptr;
+    void* dev_out = nullptr;
+    int32_t* dev_valid = nullptr;
+    std::vector<void*> bufs;
+    hipEvent_t ev_h2d0 = nullptr, ev_h2d1 = nullptr, ev_k0 = nullptr, ev_k1 = nullptr, ev_done = nullptr;
+    std::vector<hipEvent_t> layer_ev;
+    bool busy = false;
+};
+
+struct Context;
+
+struct Model {
+    Context* ctx = nullptr;
+    int id = 0;
+    int arch = 0;
+    int hyper[8] = {0};
+    int max_batch = 0;
+    std::vector<Op> ops;
+    std::vector<size_t> buf_elems;     // per-sample elements of each activation buffer
+    size_t in_elems = 0;               // per-sample fp16 input elements
+    int classes = 0;                   // CNN
+    int seq = 0, hidden = 0;           // encoder
+    std::vector<void*> dev_allocs;     // weights
+    std::vector<Instance> inst;
+    std::mutex mu;
+    int in_flight = 0;
+
+    size_t in_bytes(int b) const { return (size_t)b * in_elems * 2; }
+    size_t out_bytes(int b) const;
+    size_t out_offset(int ref, int b) const;
+};
+
+struct Ticket {
+    Model* model = nullptr;
+    int instance = 0, prio = 0, batch = 0;
+    void* host_out = nullptr;
+    strait_record rec{};
+    bool done = false;
+    int status = 0;
+};
+
+struct StreamWorker {
+    hipStream_t stream = nullptr;
+    std::thread th;
+    std::deque<Ticket*> q;
+};
+
+struct Context {
+    int device = 0;
+    std::vector<hipStream_t> hp, lp, copy;
+    std::vector<StreamWorker*> workers;     // one per compute stream: hp first, then lp
+    std::mutex mu;                          // guards worker queues, ticket completion, counters
+    std::condition_variable cv_work, cv_done;
+    bool stop = false;
+    unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;
+    int n_models = 0, next_model_id = 0;
+};
+
+int build_plan(Model& m, const void* blob, size_t bytes);
+int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed);
+
+}  // namespace strait

@@ -1,0 +1,184 @@
+"""GPU parity, kernel by kernel: each library kernel, called through the C ABI's kernel-level
+entry points on the oracle's own operands, against the oracle's operator."""
+import numpy as np
+import pytest
+
+from oracle import ops
+from parity import check_kernel
+
+pytestmark = pytest.mark.gpu
+R = np.random.default_rng(20260428)
+
+
+@pytest.fixture(scope="module")
+def S():
+    import torch
+    import paper_2604_28175_amd as strait
+    assert torch.cuda.is_available()
+    strait.torch = torch
+    return strait
+
+
+def dev(S, a, dtype=None):
+    t = S.torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def f16(a):
+    return np.asarray(a).astype(np.float16)
+
+
+def act_ref(y, act):
+    return {0: y, 1: ops.relu(y), 2: ops.relu6(y), 3: ops.gelu(y)}[act]
+
+
+CONV_CASES = [
+    # N, H, W, C, K, R, stride, pad, act, residual, out_f32     (what it exercises)
+    (2, 14, 14, 64, 64, 3, 1, 1, 1, False, False),      # gather path, exact tiles in K
+    (3, 15, 13, 32, 96, 3, 2, 1, 1, False, False),      # stride 2, ragged M, ragged N tile
+    (2, 9, 9, 16, 40, 3, 1, 1, 0, True, False),         # C = 16: a 32-wide slice straddles taps; residual
+    (1, 10, 10, 24, 72, 3, 2, 1, 2, False, False),      # C = 24, ReLU6
+    (2, 12, 12, 128, 256, 1, 1, 0, 1, True, False),     # 1x1 GEMM path + residual + ReLU
+    (2, 12, 12, 64, 128, 1, 2, 0, 0, False, False),     # strided 1x1 (projection shortcut)
+    (2, 20, 20, 3, 16, 7, 2, 3, 1, False, False),       # C = 3: scalar gather path, 7x7
+    (1, 8, 8, 5, 10, 3, 1, 1, 0, False, False),         # odd C and K: scalar gather, direct epilogue
+    (4, 1, 1, 64, 10, 1, 1, 0, 0, False, True),         # FC as 1x1 conv, fp32 logits
+    (1, 40, 40, 64, 64, 3, 1, 1, 1, False, False),      # several 128-pixel tiles and a ragged tail (M = 1600)
+    (1, 7, 7, 512, 512, 3, 1, 1, 1, False, False),      # long reduction (K = 4608), small M
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c[:8])))
+def test_conv2d(S, case):
+    N, H, W, C, K, Rk, stride, pad, act, use_res, out_f32 = case
+    x = f16(R.standard_normal((N, H, W, C)))
+    w = f16(R.standard_normal((K, C, Rk, Rk)) * (2.0 / (C * Rk * Rk)) ** 0.5)
+    b = R.standard_normal(K).astype(np.float32)
+    ref = ops.conv2d(x, w, b, stride, pad)
+    res = f16(R.standard_normal(ref.shape)) if use_res else None
+    if use_res:
+        ref = ref + res.astype(np.float64)
+    ref = act_ref(ref, act)
+    w_krsc = np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))
+    y = S.k_conv2d(dev(S, x), dev(S, w_krsc), dev(S, b), stride, pad, act, None if res is None else dev(S, res), out_f32)
+    S.torch.cuda.synchronize()
+    check_kernel(y.float().cpu().numpy(), ref, f"conv {case}")
+
+
+def test_conv2d_integer_data_is_bit_exact(S):
+    """Small integers are exact in fp16 and fp32, so the GPU must reproduce the oracle exactly."""
+    x = R.integers(-3, 4, (2, 11, 9, 16)).astype(np.float16)
+    w = R.integers(-2, 3, (24, 16, 3, 3)).astype(np.float16)
+    b = R.integers(-5, 6, 24).astype(np.float32)
+    for stride in (1, 2):
+        ref = ops.conv2d(x, w, b, stride, 1)
+        assert np.abs(ref).max() < 2048
+        y = S.k_conv2d(dev(S, x), dev(S, np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))), dev(S, b), stride, 1)
+        assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref)
+
+
+def test_conv2d_tap_count_pattern(S):
+    y = S.k_conv2d(dev(S, np.ones((1, 6, 6, 8), np.float16)), dev(S, np.ones((8, 3, 3, 8), np.float16)), None, 2, 1)
+    got = y.float().cpu().numpy()[0, :, :, 0] / 8
+    cnt = lambda i: sum(0 <= 2 * i + r - 1 < 6 for r in range(3))
+    assert np.array_equal(got, [[cnt(i) * cnt(j) for j in range(3)] for i in range(3)])
+
+
+@pytest.mark.parametrize("M,N,K,act,use_res,out_f32", [(256, 768, 768, 0, True, False), (130, 3072, 768, 3, False, False),
+                                                        (64, 768, 3072, 0, True, False), (5, 1000, 2048, 0, False, True),
+                                                        (300, 2304, 768, 0, False, False)])
+def test_gemm(S, M, N, K, act, use_res, out_f32):
+    x = f16(R.standard_normal((M, K)))
+    w = f16(R.standard_normal((N, K)) * K ** -0.5)
+    b = (R.standard_normal(N) * 0.1).astype(np.float32)
+    ref = ops.linear(x, w, b)
+    res = f16(R.standard_normal(ref.shape)) if use_res else None
+    if use_res:
+        ref = ref + res.astype(np.float64)
+    ref = act_ref(ref, act)
+    y = S.k_gemm(dev(S, x), dev(S, w), dev(S, b), act, None if res is None else dev(S, res), out_f32)
+    check_kernel(y.float().cpu().numpy(), ref, f"gemm {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("N,H,W,C,stride", [(2, 14, 14, 96, 1), (2, 15, 13, 144, 2), (1, 7, 7, 960, 1), (3, 28, 28, 32, 2), (1, 9, 10, 8, 1)])
+def test_dwconv3x3(S, N, H, W, C, stride):
+    x = f16(R.standard_normal((N, H, W, C)) * 2)
+    w = f16(R.standard_normal((C, 1, 3, 3)) * 0.47)
+    b = R.standard_normal(C).astype(np.float32)
+    ref = ops.relu6(ops.dwconv2d(x, w, b, stride, 1))
+    w_rsc = np.ascontiguousarray(np.transpose(w[:, 0], (1, 2, 0)))
+    y = S.k_dwconv3x3(dev(S, x), dev(S, w_rsc), dev(S, b), stride, S.ACT_RELU6)
+    check_kernel(y.float().cpu().numpy(), ref, "dwconv")
+    assert (ref == 6).any() and (ref == 0).any()
+
+
+def test_pools_bit_exact_and_avg(S):
+    x = f16(R.standard_normal((2, 13, 12, 64)) - 3.0)      # mostly negative: padding must never win
+    y = S.k_maxpool3x3s2(dev(S, x))
+    assert np.array_equal(y.cpu().numpy().astype(np.float64), ops.maxpool2d(x, 3, 2, 1))
+    g = S.k_global_avgpool(dev(S, x))
+    check_kernel(g.float().cpu().numpy(), ops.global_avg_pool(x.astype(np.float64)), "gap")
+    c = S.k_global_avgpool(dev(S, np.full((1, 7, 7, 8), 3.25, np.float16)))
+    assert np.array_equal(c.cpu().numpy(), np.full((1, 8), 3.25, np.float16))
+
+
+@pytest.mark.parametrize("rows,n", [(4, 10), (33, 1000), (1, 7), (5, 64)])
+def test_softmax_top1(S, rows, n):
+    x = (R.standard_normal((rows, n)) * 4).astype(np.float32)
+    x[0, min(3, n - 1)] = x[0].max() + 1.0
+    x[-1, 0] = x[-1, n - 1] = x[-1].max() + 2.0             # exact tie: lowest index wins
+    p, t = S.k_softmax_top1(dev(S, x))
+    ref = ops.softmax(x)
+    assert np.abs(p.cpu().numpy() - ref).max() < 1e-5
+    assert np.abs(p.cpu().numpy().sum(-1) - 1).max() < 1e-5
+    assert np.array_equal(t.cpu().numpy(), ops.argmax_first(x))
+    assert t.cpu().numpy()[-1] == 0
+
+
+@pytest.mark.parametrize("rows,n", [(7, 768), (130, 768), (3, 64), (2, 3072)])
+def test_layernorm(S, rows, n):
+    x = f16(R.standard_normal((rows, n)) * 3 + 1)
+    g = R.uniform(0.8, 1.2, n).astype(np.float32)
+    b = (R.standard_normal(n) * 0.02).astype(np.float32)
+    y = S.k_layernorm(dev(S, x), dev(S, g), dev(S, b), 1e-12)
+    check_kernel(y.float().cpu().numpy(), ops.layernorm(x, g, b, 1e-12), "layernorm")
+
+
+@pytest.mark.parametrize("B,Sq,heads,lens", [(3, 128, 12, (128, 32, 77)), (2, 64, 2, (64, 5)), (4, 32, 1, (1, 16, 31, 32)),
+                                             (2, 128, 4, (33, 100))])
+def test_attention(S, B, Sq, heads, lens):
+    hid = heads * 64
+    qkv = f16(R.standard_normal((B, Sq, 3 * hid)))
+    vl = np.array(lens, np.int32)
+    ref = ops.attention(qkv[..., :hid], qkv[..., hid:2 * hid], qkv[..., 2 * hid:], vl, heads)
+    out = S.k_attention(dev(S, qkv), dev(S, vl), heads).float().cpu().numpy()
+    for b in range(B):
+        L = int(vl[b])
+        check_kernel(out[b, :L], ref[b, :L], f"attention seq {b}", rel=2.0 ** -9, abs_rel=2e-3)
+        assert np.isfinite(out[b]).all()
+    # padded keys never matter: scribble over them (including non-finite values) and compare bit for bit
+    qkv2 = qkv.copy()
+    for b in range(B):
+        qkv2[b, vl[b]:, hid:] = np.float16(np.inf)
+    out2 = S.k_attention(dev(S, qkv2), dev(S, vl), heads).float().cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(out2[b, :vl[b]], out[b, :vl[b]])
+
+
+def test_argmax_f16(S):
+    x = f16(R.standard_normal((6, 16, 768)))
+    x[2, 0, 5] = x[2, 0, 700] = 50.0
+    t = S.k_argmax_f16(dev(S, x), 768, 16 * 768, 6)
+    assert np.array_equal(t.cpu().numpy(), ops.argmax_first(x[:, 0, :].astype(np.float64)))
+
+
+def test_launchers_reject_bad_shapes(S):
+    x = dev(S, np.zeros((1, 8, 8, 12), np.float16))
+    with pytest.raises(S.StraitError):
+        S.k_dwconv3x3(x, dev(S, np.zeros((3, 3, 12), np.float16)), None, 1)       # C % 8 != 0
+    with pytest.raises(S.StraitError):
+        S.k_attention(dev(S, np.zeros((1, 48, 192), np.float16)), dev(S, np.array([48], np.int32)), 1)   # S % 32 != 0
+    with pytest.raises(S.StraitError):
+        S.k_layernorm(dev(S, np.zeros((2, 12), np.float16)), dev(S, np.ones(12, np.float32)), dev(S, np.zeros(12, np.float32)), 1e-5)

@@ -1,0 +1,138 @@
+"""GPU parity, end to end: every served architecture through the C ABI (submit at a priority ->
+pinned H2D -> kernel sequence -> D2H -> record) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import models as omodels
+from parity import check_kernel, check_logits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2604_28175_amd as strait
+    c = strait.Context(device=0, n_hp=1, n_lp=1, n_copy=2)
+    c.S = strait
+    yield c
+    c.close()
+
+
+def run_cnn(ctx, md, x, fwd, prio, what):
+    S = ctx.S
+    m = ctx.load(synth.pack(md), max_batch=x.shape[0], n_instances=1)
+    try:
+        out, rec = m.infer(x, prio=prio)
+        ref = fwd(md.tensors, x)
+        err, scale, ties = check_logits(out["logits"], ref.logits, out["top1"], what)
+        assert np.abs(out["probs"] - ref.probs).max() <= 2e-2
+        assert np.abs(out["probs"].sum(-1) - 1).max() < 1e-4
+        assert rec.batch == x.shape[0] and rec.priority == prio
+        assert rec.h2d_ms > 0 and rec.kernel_ms > 0 and rec.total_ms >= rec.kernel_ms
+        assert rec.t_enqueue_ns <= rec.t_issued_ns <= rec.t_done_ns
+        print(f"{what}: max|err| {err:.3e} of scale {scale:.3e} ({err / scale:.2e}), ties {ties}, kernels {rec.kernel_ms:.3f} ms")
+        return m, out, ref
+    except Exception:
+        m.free()
+        raise
+
+
+def test_tiny_cnn_config(ctx):
+    md = synth.tiny_cnn(synth.SEEDS[synth.ARCH_TINY_CNN])
+    x = synth.default_image_batch(md, 4, synth.SEEDS[synth.ARCH_TINY_CNN] + 4)
+    m, out, ref = run_cnn(ctx, md, x, omodels.tiny_cnn_forward, ctx.S.PRIO_HIGH, "tiny CNN b4")
+    # zero input: zero biases -> logits exactly 0, uniform probabilities
+    z, _ = m.infer(np.zeros_like(x))
+    assert not z["logits"].any() and np.allclose(z["probs"], 0.1, atol=1e-6) and not z["top1"].any()
+    m.free()
+
+
+@pytest.mark.parametrize("hw,batch", [(64, 5), (224, 2)])
+def test_resnet50(ctx, hw, batch):
+    md = synth.resnet50(synth.SEEDS[synth.ARCH_RESNET50], hw=hw)
+    x = synth.default_image_batch(md, batch, synth.SEEDS[synth.ARCH_RESNET50] + batch)
+    m, out, ref = run_cnn(ctx, md, x, omodels.resnet50_forward, ctx.S.PRIO_HIGH, f"ResNet-50 {hw}px b{batch}")
+    m.free()
+
+
+def test_resnet50_layers_and_batch_independence(ctx):
+    """Every layer's activation against the oracle's (catches wiring errors that cancel in the
+    logits), and sample i of a batch equals the same image run alone."""
+    md = synth.resnet50(3, hw=64)
+    x = synth.default_image_batch(md, 3, 8)
+    m = ctx.load(synth.pack(md), max_batch=3, n_instances=1)
+    ref = omodels.resnet50_forward(md.tensors, x, keep=True)
+    m.copy_in(0, ctx.S.PRIO_LOW, x)
+    names = {}
+    for i, li in enumerate(m.layers()):
+        names[li.name.decode()] = i
+    checked = 0
+    for lname, act in ref.trace.acts.items():
+        key = lname.replace(".out", ".c3")       # the fused epilogue of c3 produces the block output
+        if lname.endswith(".c3") or key not in names or lname in ("fc",):
+            continue
+        got = m.read_activation(0, names[key], 3).astype(np.float64).reshape(act.shape)
+        check_kernel(got, act, f"layer {lname}", rel=2.0 ** -8, abs_rel=1e-2)
+        checked += 1
+    assert checked >= 40
+    full, _ = m.infer(x, prio=ctx.S.PRIO_LOW)
+    for i in range(3):
+        one, _ = m.infer(x[i:i + 1], prio=ctx.S.PRIO_LOW)
+        assert np.abs(one["logits"][0] - full["logits"][i]).max() <= 1e-3 * np.abs(full["logits"]).max()
+        assert one["top1"][0] == full["top1"][i]
+    m.free()
+
+
+@pytest.mark.parametrize("hw,batch", [(64, 5), (224, 2)])
+def test_mobilenet_v2(ctx, hw, batch):
+    md = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2], hw=hw)
+    x = synth.default_image_batch(md, batch, synth.SEEDS[synth.ARCH_MOBILENETV2] + batch)
+    m, out, ref = run_cnn(ctx, md, x, omodels.mobilenet_v2_forward, ctx.S.PRIO_LOW, f"MobileNetV2 {hw}px b{batch}")
+    m.free()
+
+
+@pytest.mark.parametrize("kw,batch", [(dict(layers=2, hidden=128, heads=2, ffn=256, seq=64), 3),
+                                      (dict(), 2)])
+def test_encoder(ctx, kw, batch):
+    md = synth.encoder(synth.SEEDS[synth.ARCH_ENCODER], **kw)
+    x, vl = synth.token_batch(md, batch, synth.SEEDS[synth.ARCH_ENCODER] + batch, min_len=32)
+    m = ctx.load(synth.pack(md), max_batch=batch, n_instances=1)
+    out, rec = m.infer(x, vl, prio=ctx.S.PRIO_LOW)
+    ref = omodels.encoder_forward(md.tensors, x, vl, md.hyper)
+    scale = max(float(np.abs(ref.logits[b, :vl[b]]).max()) for b in range(batch))
+    worst = 0.0
+    for b in range(batch):
+        L = int(vl[b])
+        got = out["hidden"][b, :L].astype(np.float64)
+        assert np.isfinite(got).all()
+        worst = max(worst, float(np.abs(got - ref.logits[b, :L]).max()))
+    assert worst <= 2e-2 * scale, f"encoder: max|err| {worst:.3e} > 2e-2 * {scale:.3e}"
+    # top-1 of token 0 (same tie rule as the classifiers)
+    check_logits(out["hidden"][:, 0, :], ref.logits[:, 0, :], out["top1"], "encoder token 0")
+    print(f"encoder {md.hyper} b{batch}: max|err| {worst:.3e} of {scale:.3e}, kernels {rec.kernel_ms:.3f} ms")
+    m.free()
+
+
+def test_submit_errors_and_pool(ctx):
+    S = ctx.S
+    md = synth.tiny_cnn(1)
+    m = ctx.load(synth.pack(md), max_batch=2, n_instances=2)
+    x = synth.default_image_batch(md, 2, 1)
+    outs = [m.new_output(2) for _ in range(3)]
+    t0 = m.submit(S.PRIO_HIGH, x, None, outs[0])
+    t1 = m.submit(S.PRIO_LOW, x, None, outs[1])
+    assert m.try_submit(S.PRIO_LOW, x, None, outs[2]) is None            # both instances taken: E_BUSY, never blocks
+    with pytest.raises(S.StraitError) as e:
+        m.free()
+    assert e.value.status == S.E_BUSY
+    r0, r1 = m.wait(t0), m.wait(t1)
+    assert {r0.instance, r1.instance} == {0, 1} and r0.priority == S.PRIO_HIGH and r1.priority == S.PRIO_LOW
+    assert np.array_equal(outs[0], outs[1])                              # same input, either priority: same bits
+    with pytest.raises(S.StraitError) as e:
+        m.submit(S.PRIO_HIGH, synth.default_image_batch(md, 3, 1), None, m.new_output(2))
+    assert e.value.status == S.E_BATCH
+    m.free()
+    with pytest.raises(S.StraitError) as e:
+        ctx.load(b"STRX" + bytes(100), 1, 1)
+    assert e.value.status == S.E_FORMAT
