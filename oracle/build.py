@@ -18,7 +18,7 @@ def build(force: bool = True) -> str:
     base = ["gcc", "-O2", "-ftree-vectorize", "-mavx2", "-mfma", "-fopenmp", "-fPIC", "-std=c11", "-c", src]
     o64 = os.path.join(HERE, "ops_f64.o")
     o32 = os.path.join(HERE, "ops_f32.o")
-    subprocess.check_call(base + ["-DREAL=double", "-DSUFFIX=f64", "-o", o64])
+    subprocess.check_call(base + ["-DREAL=double", "-DSUFFIX=f64", "-DORACLE_COMMON", "-o", o64])
     subprocess.check_call(base + ["-DREAL=float", "-DSUFFIX=f32", "-o", o32])
     subprocess.check_call(["gcc", "-shared", "-fopenmp", "-o", LIB, o64, o32, "-lm"])
     os.remove(o64)

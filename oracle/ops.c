@@ -31,6 +31,11 @@
 
 typedef REAL real;
 
+#ifdef ORACLE_COMMON
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#endif
+
 void FN(oracle_conv2d)(const real* x, int N, int H, int W, int C,
                        const float* w /* [R][S][C][K] */, const real* b /* [K] or NULL */,
                        int K, int R, int S, int stride, int pad, real* y)

@@ -35,6 +35,11 @@ def _ptr(a):
     return None if a is None else a.ctypes.data_as(_P)
 
 
+def num_threads() -> int:
+    """OpenMP threads the C loops run on."""
+    return int(_lib.oracle_num_threads())
+
+
 def out_size(h: int, k: int, stride: int, pad: int) -> int:
     return (h + 2 * pad - k) // stride + 1
 
