@@ -24,9 +24,46 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+# The co-location phase uses five streams; with HIP's default of 4 hardware queues per process two
+# of them would share a queue and serialise.  Must be set before the HIP runtime initialises.
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
 
 MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
 HBM_PEAK_GBS = 8000.0
+
+
+def colocation(ctx, md_resnet, blob_resnet, seconds):
+    """High-priority ResNet-50 b8 requests, Poisson at 200/s, next to low-priority MobileNetV2 b64
+    issued back to back; per-request latency solo vs co-located, with and without wave priority."""
+    import synth
+    from paper_2604_28175_amd import colocate
+
+    seed = synth.SEEDS["colocation"]
+    hp = ctx.load(blob_resnet, max_batch=8, n_instances=4)
+    md_lp = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2])
+    lp = ctx.load(synth.pack(md_lp), max_batch=64, n_instances=1)
+    hp_x = [synth.default_image_batch(md_resnet, 8, seed + i) for i in range(4)]
+    lp_x = [synth.default_image_batch(md_lp, 64, seed + 100 + i) for i in range(2)]
+    arrivals = synth.poisson_arrivals_ns(seed, 200.0, seconds)
+    res = {"hp": "resnet50_v1.5 b8, Poisson 200 req/s, open loop", "lp": "mobilenet_v2 b64, back to back",
+           "seconds_per_phase": seconds}
+    colocate.run(hp, hp_x, arrivals[:50], lp, lp_x, "hp_solo")            # warm-up
+    h, _ = colocate.run(hp, hp_x, arrivals, lp, lp_x, "hp_solo")
+    res["hp_solo"] = h.summary()
+    _, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "lp_solo", lp_solo_s=min(seconds, 1.0))
+    res["lp_solo"] = l.summary()
+    h, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "both")
+    res["colocated"] = {"hp": h.summary(), "lp": l.summary()}
+    ctx.set_wave_priority(False)
+    h, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "both")
+    res["colocated_no_wave_priority"] = {"hp": h.summary(), "lp": l.summary()}
+    ctx.set_wave_priority(True)
+    solo, co = res["hp_solo"]["latency_ms"], res["colocated"]["hp"]["latency_ms"]
+    res["hp_p99_colocated_over_solo"] = round(co["p99"] / solo["p99"], 3)
+    res["hp_p50_colocated_over_solo"] = round(co["p50"] / solo["p50"], 3)
+    hp.free()
+    lp.free()
+    return res
 
 
 def main() -> int:
@@ -37,6 +74,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-batch", action="store_true")
+    ap.add_argument("--colocation-seconds", type=float, default=2.0,
+                    help="length of each phase of the dual-priority co-location run (0 = skip)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images the CPU oracle is timed on (0 = twelve per thread)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -130,6 +169,9 @@ def main() -> int:
         out["by_batch"] = by
 
     model.free()
+
+    if args.colocation_seconds > 0:
+        out["colocation"] = colocation(ctx, md, blob, args.colocation_seconds)
     ctx.close()
 
     if not args.no_cpu_baseline:

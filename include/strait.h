@@ -118,6 +118,10 @@ int32_t strait_version(void);
 
 strait_status strait_ctx_create(const strait_ctx_desc* desc, strait_ctx** out);
 strait_status strait_ctx_destroy(strait_ctx* ctx);      /* E_BUSY while models are loaded   */
+/* Whether kernels of high-priority batches raise their wave priority (default on).  Turning it
+ * off leaves the two levels distinguished by their streams only: the A/B for the paper's
+ * ablation "without stream priority" (Appendix A.3). */
+strait_status strait_ctx_set_wave_priority(strait_ctx* ctx, int32_t enabled);
 
 strait_status strait_model_load(strait_ctx* ctx, const strait_model_desc* desc, strait_model** out);
 strait_status strait_model_free(strait_model* m);       /* E_BUSY with batches in flight    */

@@ -113,6 +113,15 @@ strait_status strait_ctx_destroy(strait_ctx* c) {
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_wave_priority(strait_ctx* c, int32_t enabled) {
+    if (!c) { set_error("ctx_set_wave_priority: null"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->wave_priority = enabled != 0;
+    return STRAIT_OK;
+}
+
+static int hp_flag(const Context* c, int prio) { return prio == STRAIT_PRIO_HIGH && c->wave_priority; }
+
 static void free_instance(Instance& in) {
     if (in.pinned_in) (void)hipHostFree(in.pinned_in);
     if (in.pinned_out) (void)hipHostFree(in.pinned_out);
@@ -289,7 +298,7 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
     rc = hipSetDevice(c->device) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = enqueue_h2d(m, in, batch, host_in, valid_len, cs, s);
     if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = run_plan(*m, in, batch, s, prio == STRAIT_PRIO_HIGH, -1, false);
+    if (!rc) rc = run_plan(*m, in, batch, s, hp_flag(c, prio), -1, false);
     if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
@@ -356,7 +365,7 @@ strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio
     int rc = check_call(m, instance, prio, batch);
     if (rc) return rc;
     HIP_TRY(hipSetDevice(m->ctx->device));
-    return run_plan(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), prio == STRAIT_PRIO_HIGH, -1, false);
+    return run_plan(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), hp_flag(m->ctx, prio), -1, false);
 }
 
 strait_status strait_copy_out(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, void* host_out) {
@@ -387,7 +396,7 @@ strait_status strait_run_timed(strait_model* m, int32_t instance, strait_priorit
     Instance& in = m->inst[instance];
     hipStream_t s = compute_stream(m->ctx, prio, instance);
     HIP_TRY(hipSetDevice(m->ctx->device));
-    rc = run_plan(*m, in, batch, s, prio == STRAIT_PRIO_HIGH, -1, true);
+    rc = run_plan(*m, in, batch, s, hp_flag(m->ctx, prio), -1, true);
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(s));
     for (size_t i = 0; i < m->ops.size(); ++i) HIP_TRY(hipEventElapsedTime(&layer_ms[i], in.layer_ev[i], in.layer_ev[i + 1]));

@@ -109,6 +109,7 @@ struct Context {
     std::mutex mu;                          // guards worker queues, ticket completion, counters
     std::condition_variable cv_work, cv_done;
     bool stop = false;
+    bool wave_priority = true;
     unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;
     int n_models = 0, next_model_id = 0;
 };
