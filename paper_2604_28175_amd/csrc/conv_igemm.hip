@@ -257,6 +257,289 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const ConvParams p) {
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Deep-pipelined variant for the regular cases: dense 1x1 / GEMM, and filters whose channel count
+// is a multiple of the 32-wide slice (so a slice never straddles two filter taps).
+//
+// The kernel above keeps one slice in flight per workgroup and spends most of its issue slots on
+// per-lane gather arithmetic.  Here
+//   - slices travel global -> LDS directly (buffer_load_dwordx4 ... lds: each lane names a 16-byte
+//     chunk, the wave's 64 chunks land in 1 KB of consecutive LDS) through a ring of STAGES
+//     buffers, STAGES-1 slices in flight, one barrier per slice;
+//   - the address of a chunk is split into a per-lane part fixed for the whole kernel (pixel or
+//     channel row, chunk within the slice) held in a VGPR, and a part that is the same for the
+//     whole workgroup (filter tap, channel base of the slice) kept in a scalar register and
+//     advanced by scalar instructions: a weight load costs no vector instruction at all, an input
+//     load one bit test and one select;
+//   - whether tap (r,s) of an output pixel falls inside the image is precomputed per lane as a bit
+//     mask over the taps; a tap outside, a row beyond M or a channel beyond Cout gets the offset
+//     0x80000000, which the buffer's range check turns into zeros in LDS (no stale data, no branch);
+//   - the hardware fixes the LDS position of lane i's chunk, so the bank-conflict-avoiding layout
+//     is obtained from the other side: rows are 64 bytes (4 chunks) and lane i fetches logical
+//     chunk (i & 3) ^ ((i >> 4) & 3) of its row, i.e. LDS holds chunk c of row r at position
+//     c ^ ((r >> 2) & 3); any 16 consecutive rows read at one logical chunk then touch 16
+//     distinct 16-byte bank groups;
+//   - the loads are issued from inline assembly so that the waits are ours: "all but the newest
+//     STAGES-2 slices have landed" before the barrier, rather than a wait for everything.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+constexpr unsigned OOB_OFFSET = 0x80000000u;       // beyond any buffer this kernel accepts
+
+__device__ __forceinline__ intx4 make_rsrc(const void* base, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)base;
+    intx4 r;
+    r[0] = (int)(unsigned)a;
+    r[1] = (int)((unsigned)(a >> 32) & 0xffffu);   // stride 0: raw buffer
+    r[2] = (int)bytes;                              // num_records in bytes
+    r[3] = 0x00020000;                              // 32-bit data format, offsets in bytes
+    return r;
+}
+
+// One wave-wide transfer of 64 x 16 bytes: lane i's chunk at rsrc.base + voff + soff goes to
+// LDS byte address lds_base + 16 i; lanes whose voff is out of range deposit zeros.
+__device__ __forceinline__ void dma16(intx4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(m0v), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_then_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int BK, int WGM, int MODE, int STAGES, bool GELU>
+__global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p) {
+    constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
+    constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
+    constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
+    constexpr int WGN = 4 / WGM;                       // the 4 waves form a WGM x WGN grid over the tile
+    constexpr int TM = BM / WGM, TN = BN / WGN;
+    constexpr int TMB = TM / 32, TNB = TN / 32;
+    constexpr int XI = BM / (4 * RPI), WI = BN / (4 * RPI);   // transfers per wave per slice
+    static_assert((BK == 32 || BK == 64) && TM % 32 == 0 && TN % 32 == 0 && XI >= 1 && WI >= 1, "unsupported tile");
+    constexpr int STAGE = (BM + BN) * BK;              // halfs per stage
+    constexpr int LDC = BN + 8;
+    static_assert(MODE == MODE_1X1 || MODE == MODE_GATHER8, "vector modes only");
+    static_assert(STAGES >= 2 && STAGES * STAGE * 2 <= 160 * 1024 && BM * LDC * 2 <= 160 * 1024, "LDS limit");
+
+    extern __shared__ __attribute__((aligned(1024))) half_t smem[];    // max(STAGES * STAGE, BM * LDC) halfs
+    const unsigned lds0 = (unsigned)(uintptr_t)smem;
+
+    if (p.hp) __builtin_amdgcn_s_setprio(3);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave % WGM) * TM, wn0 = (wave / WGM) * TN;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    const int tiles_n = (p.Cout + BN - 1) / BN;
+    int logical;
+    {
+        const int nb = gridDim.x, b = blockIdx.x;
+        const int per = nb >> 3, rem = nb & 7, xcd = b & 7, idx = b >> 3;
+        logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
+    const int m0 = (logical / tiles_n) * BM;
+    const int n0 = (logical % tiles_n) * BN;
+
+    // The input buffer starts `lead` elements before x so that the per-lane offset of an output
+    // pixel (its window's top-left tap, which may lie in the padding) is never negative.
+    const long long lead = (long long)p.pad_h * p.sH + (long long)p.pad_w * p.sW;
+    const intx4 xrsrc = make_rsrc(p.x - lead, (unsigned)((p.x_elems + lead) * 2));
+    const intx4 wrsrc = make_rsrc(p.w, (unsigned)((long long)p.Cout * p.ldw * 2));
+
+    // ---- per-lane constants: row (lane >> 2) of each 16-row group, logical chunk cl ---------------
+    const int rsub = lane / CPRW;
+    const int cl = (lane % CPRW) ^ (((wave * RPI + rsub) / SWD) & (CPRW - 1));
+    unsigned xoff[XI], tapmask[XI];
+#pragma unroll
+    for (int j = 0; j < XI; ++j) {
+        const int m = m0 + (j * 4 + wave) * RPI + rsub;
+        xoff[j] = OOB_OFFSET;
+        tapmask[j] = 0xffffffffu;
+        if (m < p.M) {
+            if (MODE == MODE_1X1 && p.stride_h == 1) {
+                xoff[j] = (unsigned)(((long long)m * p.sW + cl * 8) * 2);
+            } else {
+                const int n = m / p.PQ, rem = m - n * p.PQ;
+                const int pp = rem / p.Q, qq = rem - pp * p.Q;
+                const int ih0 = pp * p.stride_h - p.pad_h, iw0 = qq * p.stride_w - p.pad_w;
+                xoff[j] = (unsigned)(((long long)n * p.sN + (long long)(pp * p.stride_h) * p.sH +
+                                      (long long)(qq * p.stride_w) * p.sW + cl * 8) * 2);
+                if (MODE == MODE_GATHER8) {
+                    unsigned mask = 0;
+                    for (int rr = 0; rr < p.R; ++rr)
+                        for (int ss = 0; ss < p.S; ++ss)
+                            if ((unsigned)(ih0 + rr) < (unsigned)p.H && (unsigned)(iw0 + ss) < (unsigned)p.W)
+                                mask |= 1u << (rr * p.S + ss);
+                    tapmask[j] = mask;
+                }
+            }
+        }
+    }
+    unsigned woff[WI];
+#pragma unroll
+    for (int j = 0; j < WI; ++j) {
+        const int n = n0 + (j * 4 + wave) * RPI + rsub;
+        woff[j] = n < p.Cout ? (unsigned)(((long long)n * p.ldw + cl * 8) * 2) : OOB_OFFSET;
+    }
+
+    // ---- workgroup-uniform position of the slice being issued ---------------------------------
+    const int nk = (p.Kg + BK - 1) / BK;
+    const bool ragged_k = (p.Kg & (BK - 1)) != 0;      // only possible for 1x1 / GEMM
+    int ki = 0;                                        // slice index
+    int tap = 0, ts = 0, cb = 0;                       // filter tap, its column, channel base
+    unsigned tap_off = 0;                              // byte offset of the tap: (r*sH + s*sW) * 2
+    const unsigned row_step = (unsigned)(p.sH - p.S * p.sW) * 2u;   // from the end of a filter row to the next
+
+    auto issue = [&](int stage) {
+        const unsigned sx = lds0 + (unsigned)(stage * STAGE) * 2u;
+        const unsigned sw = sx + (unsigned)(BM * BK) * 2u;
+        const bool live = ki < nk;                     // slices past the end deposit zeros
+        const unsigned soff_x = MODE == MODE_1X1 ? (unsigned)ki * (BK * 2) : tap_off + (unsigned)cb * 2u;
+#pragma unroll
+        for (int j = 0; j < XI; ++j) {
+            unsigned v = xoff[j];
+            if (MODE == MODE_GATHER8) v = ((tapmask[j] >> tap) & 1u) ? v : OOB_OFFSET;
+            if (MODE == MODE_1X1 && ragged_k) v = (ki * BK + cl * 8 < p.Kg) ? v : OOB_OFFSET;
+            if (!live) v = OOB_OFFSET;
+            dma16(xrsrc, v, live ? soff_x : 0u, sx + (unsigned)((j * 4 + wave) * 1024));
+        }
+#pragma unroll
+        for (int j = 0; j < WI; ++j)
+            dma16(wrsrc, live ? woff[j] : OOB_OFFSET, live ? (unsigned)ki * (BK * 2) : 0u, sw + (unsigned)((j * 4 + wave) * 1024));
+        ++ki;
+        if (MODE == MODE_GATHER8) {
+            cb += BK;
+            if (cb >= p.C) {
+                cb = 0;
+                ++tap;
+                tap_off += (unsigned)p.sW * 2u;
+                if (++ts == p.S) { ts = 0; tap_off += row_step; }
+            }
+        }
+    };
+
+    floatx16 acc[TNB][TMB];
+#pragma unroll
+    for (int a = 0; a < TNB; ++a)
+#pragma unroll
+        for (int b = 0; b < TMB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+#pragma unroll
+    for (int i = 0; i < STAGES - 1; ++i) issue(i);
+
+    // MFMA operand fragments are double-buffered in registers: the LDS reads of 16-wide step ks+1
+    // are in flight while the MFMAs of step ks issue.
+    const int swz = (l32 / SWD) & (CPRW - 1);
+    constexpr int KS = BK / 16;
+    int rd = 0, wr = STAGES - 1;
+    for (int kt = 0; kt < nk; ++kt) {
+        wait_loads_then_barrier<(STAGES - 2) * (XI + WI)>();   // slice kt has landed everywhere; buffer wr is free
+        const half_t* Xs = smem + rd * STAGE;
+        const half_t* Ws = Xs + BM * BK;
+        half8 wf[2][TNB], xf[2][TMB];
+        auto load_frags = [&](int buf, int ks) {
+            const int pos = ((ks * 2 + lh) ^ swz) * 8;
+#pragma unroll
+            for (int a = 0; a < TNB; ++a) wf[buf][a] = *(const half8*)(Ws + (wn0 + a * 32 + l32) * BK + pos);
+#pragma unroll
+            for (int b = 0; b < TMB; ++b) xf[buf][b] = *(const half8*)(Xs + (wm0 + b * 32 + l32) * BK + pos);
+        };
+        load_frags(0, 0);
+        issue(wr);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) load_frags((ks + 1) & 1, ks + 1);
+#pragma unroll
+            for (int a = 0; a < TNB; ++a)
+#pragma unroll
+                for (int b = 0; b < TMB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b], 0, 0, 0);
+        }
+        rd = rd + 1 == STAGES ? 0 : rd + 1;
+        wr = wr + 1 == STAGES ? 0 : wr + 1;
+    }
+    wait_loads_then_barrier<0>();                      // trailing transfers have landed; LDS is free
+
+    // ---- epilogue (same as the first kernel's staged path) --------------------------------------
+    // ReLU / ReLU6 / none are one clamp with workgroup-uniform bounds; GELU is a separate instantiation
+    half_t* Cs = smem;
+    const bool fuse_act = (p.res == nullptr);
+    const float lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? 0.f : -INFINITY;
+    const float hi = p.act == ACT_RELU6 ? 6.f : INFINITY;
+    auto activate = [&](float v) {
+        if (GELU) v = 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+        return fminf(fmaxf(v, lo), hi);
+    };
+#pragma unroll
+    for (int a = 0; a < TNB; ++a)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int cn = wn0 + a * 32 + 8 * g + 4 * lh;
+            float bv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = (p.bias && (n0 + cn + j) < p.Cout) ? p.bias[n0 + cn + j] : 0.f;
+#pragma unroll
+            for (int b = 0; b < TMB; ++b) {
+                half4 h;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float v = acc[a][b][4 * g + j] + bv[j];
+                    if (fuse_act) v = activate(v);
+                    h[j] = (half_t)v;
+                }
+                *(half4*)(Cs + (wm0 + b * 32 + l32) * LDC + cn) = h;
+            }
+        }
+    __syncthreads();
+    constexpr int CPR = BN / 8;
+#pragma unroll
+    for (int i = 0; i < BM * CPR / 256; ++i) {
+        const int id = tid + i * 256;
+        const int row = id / CPR, c8 = id - row * CPR;
+        const int m = m0 + row, n = n0 + c8 * 8;
+        if (m < p.M && n < p.Cout) {
+            half8 v = *(const half8*)(Cs + row * LDC + c8 * 8);
+            if (!fuse_act) {
+                const half8 rv = *(const half8*)(p.res + (long long)m * p.ldy + n);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = (half_t)activate((float)v[j] + (float)rv[j]);
+            }
+            *(half8*)((half_t*)p.y + (long long)m * p.ldy + n) = v;
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int STAGES>
+static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
+    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN);
+    if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
+    constexpr unsigned ring = STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
+    constexpr unsigned lds = ring > ctile ? ring : ctile;    // the epilogue parks the output tile in the same LDS
+    dim3 grid((unsigned)tiles), block(256);
+    auto go = [&](auto kernel) -> int {
+        static bool configured = false;                 // one flag per instantiation
+        if (!configured && lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
+        }
+        configured = true;
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
+        return 0;
+    };
+    int rc;
+    if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_1X1, STAGES, true>);
+    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_1X1, STAGES, false>);
+    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_GATHER8, STAGES, false>);
+    if (rc) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
+    return 0;
+}
+
 template <int BM, int BN>
 static int launch_tile(const ConvParams& p, int mode, bool staged, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN);
@@ -272,7 +555,8 @@ static int launch_tile(const ConvParams& p, int mode, bool staged, hipStream_t s
     return 0;
 }
 
-int launch_conv(const ConvParams& p, hipStream_t stream) {
+int launch_conv(const ConvParams& params, hipStream_t stream) {
+    ConvParams p = params;
     if (!p.x || !p.w || !p.y || p.M <= 0 || p.Cout <= 0 || p.Kg <= 0 || p.C <= 0 || p.R <= 0 || p.S <= 0 ||
         p.Q <= 0 || p.PQ <= 0 || p.stride_h <= 0 || p.stride_w <= 0) {
         set_error("conv: invalid parameters"); return -1;
@@ -290,6 +574,29 @@ int launch_conv(const ConvParams& p, hipStream_t stream) {
     const bool staged = !p.out_f32 && (p.Cout % 8 == 0) && (p.ldy % 8 == 0);
     // pick the largest tile that still gives the 256 CUs about two workgroups each
     auto tiles = [&](int bm, int bn) { return (long long)((p.M + bm - 1) / bm) * ((p.Cout + bn - 1) / bn); };
+    const bool dense = mode == MODE_1X1 && p.stride_h == 1;
+    p.x_elems = dense ? (long long)p.M * p.sW : (long long)(p.M / p.PQ) * p.sN;
+    const long long lead = (long long)p.pad_h * p.sH + (long long)p.pad_w * p.sW;
+    const bool small = (p.x_elems + lead) * 2 <= 0x7fffffffLL && (long long)p.Cout * p.ldw * 2 <= 0x7fffffffLL;
+    const bool regular = mode == MODE_1X1 || (mode == MODE_GATHER8 && p.C % 32 == 0 && p.R * p.S <= 32 && p.act != ACT_GELU);
+    if (staged && regular && small) {
+        // Tile choice, from sweeps over the served networks' layer shapes on MI355X:
+        //  - deep reductions (K >= 512) with at least 128 output channels are limited by how fast
+        //    operands reach the CU: the 128x128 tile halves the bytes per flop and 64-wide slices
+        //    halve the barriers; a third stage is affordable when there are at most two tiles per CU;
+        //  - shallow reductions stream activations: the 128x64 tile with few stages keeps the LDS
+        //    footprint small, i.e. more workgroups in flight per CU to cover memory latency.
+        const bool bk64 = mode == MODE_1X1 ? p.Kg % 64 == 0 : p.C % 64 == 0;
+        const long long t128 = tiles(128, 128), t64 = tiles(128, 64);
+        if (p.Kg >= 512 && p.Cout >= 128 && t128 >= 192) {
+            if (bk64) return t128 <= 512 ? launch_dma_tile<128, 128, 64, 2, 3>(p, mode, stream)
+                                         : launch_dma_tile<128, 128, 64, 2, 2>(p, mode, stream);
+            return launch_dma_tile<128, 128, 32, 2, 3>(p, mode, stream);
+        }
+        if (t64 >= 256) return p.Kg >= 288 ? launch_dma_tile<128, 64, 32, 2, 3>(p, mode, stream)
+                                           : launch_dma_tile<128, 64, 32, 2, 2>(p, mode, stream);
+        return launch_dma_tile<64, 64, 32, 2, 2>(p, mode, stream);
+    }
     if (p.Cout > 64 && tiles(128, 128) >= 512) return launch_tile<128, 128>(p, mode, staged, stream);
     if (tiles(128, 64) >= 512) return launch_tile<128, 64>(p, mode, staged, stream);
     return launch_tile<64, 64>(p, mode, staged, stream);

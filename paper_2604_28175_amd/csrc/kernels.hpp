@@ -35,6 +35,7 @@ struct ConvParams {
     int act;
     int out_f32;
     int hp;                  // raise wave priority (high-priority batch)
+    long long x_elems;       // extent of x in elements; filled in by launch_conv
 };
 
 int launch_conv(const ConvParams& p, hipStream_t stream);
