@@ -128,6 +128,7 @@ static void free_instance(Instance& in) {
     if (in.dev_in) (void)hipFree(in.dev_in);
     if (in.dev_out) (void)hipFree(in.dev_out);
     if (in.dev_valid) (void)hipFree(in.dev_valid);
+    if (in.splitk_ws) (void)hipFree(in.splitk_ws);
     for (void* b : in.bufs) if (b) (void)hipFree(b);
     hipEvent_t evs[5] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
@@ -159,7 +160,8 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
         bool ok = hipHostMalloc(&in.pinned_in, inb + (size_t)d->max_batch * 4, hipHostMallocDefault) == hipSuccess &&
                   hipHostMalloc(&in.pinned_out, outb, hipHostMallocDefault) == hipSuccess &&
                   hipMalloc(&in.dev_in, inb) == hipSuccess && hipMalloc(&in.dev_out, outb) == hipSuccess &&
-                  hipMalloc((void**)&in.dev_valid, (size_t)d->max_batch * 4 + 256) == hipSuccess;
+                  hipMalloc((void**)&in.dev_valid, (size_t)d->max_batch * 4 + 256) == hipSuccess &&
+                  hipMalloc((void**)&in.splitk_ws, SPLITK_WS_BYTES) == hipSuccess;
         for (size_t i = 0; ok && i < m->buf_elems.size(); ++i) {
             void* b = nullptr;
             const size_t bytes = (m->buf_elems[i] * 2 * (size_t)d->max_batch + 255) / 256 * 256;
@@ -450,8 +452,14 @@ strait_status strait_k_conv2d(void* stream, const void* x, int32_t N, int32_t H,
         if (e != hipSuccess) { (void)hipFree(tmp); set_error("conv2d: padding the weights failed: %s", hipGetErrorString(e)); return STRAIT_E_HIP; }
         p.w = (const half_t*)tmp;
     }
+    // small problems may take the split-K path, which needs an fp32 workspace
+    void* ws = nullptr;
+    if ((long long)p.M * K <= 128LL * 4096) {
+        if (hipMalloc(&ws, SPLITK_WS_BYTES) != hipSuccess) { (void)hipGetLastError(); ws = nullptr; }
+        p.ws = (float*)ws; p.ws_bytes = ws ? SPLITK_WS_BYTES : 0;
+    }
     int rc = launch_conv(p, (hipStream_t)stream);
-    if (tmp) { (void)hipStreamSynchronize((hipStream_t)stream); (void)hipFree(tmp); }
+    if (tmp || ws) { (void)hipStreamSynchronize((hipStream_t)stream); if (tmp) (void)hipFree(tmp); if (ws) (void)hipFree(ws); }
     return rc;
 }
 
@@ -463,7 +471,14 @@ strait_status strait_k_gemm(void* stream, const void* x, const void* w, const fl
     p.M = M; p.PQ = 1; p.Q = 1; p.H = 1; p.W = 1; p.C = K; p.R = 1; p.S = 1;
     p.stride_h = p.stride_w = 1; p.pad_h = p.pad_w = 0;
     p.sN = K; p.sH = K; p.sW = K; p.Kg = K; p.ldw = K; p.Cout = N; p.ldy = N; p.act = act; p.out_f32 = out_f32; p.hp = hp;
-    return launch_conv(p, (hipStream_t)stream);
+    void* ws = nullptr;
+    if ((long long)M * N <= 128LL * 4096) {
+        if (hipMalloc(&ws, SPLITK_WS_BYTES) != hipSuccess) { (void)hipGetLastError(); ws = nullptr; }
+        p.ws = (float*)ws; p.ws_bytes = ws ? SPLITK_WS_BYTES : 0;
+    }
+    int rc = launch_conv(p, (hipStream_t)stream);
+    if (ws) { (void)hipStreamSynchronize((hipStream_t)stream); (void)hipFree(ws); }
+    return rc;
 }
 
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,

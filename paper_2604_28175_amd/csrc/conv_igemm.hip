@@ -339,8 +339,12 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
         const int per = nb >> 3, rem = nb & 7, xcd = b & 7, idx = b >> 3;
         logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
-    const int m0 = (logical / tiles_n) * BM;
-    const int n0 = (logical % tiles_n) * BN;
+    // split-K: the grid holds ksplit copies of the tile grid; copy z reduces slices [k_begin, k_end)
+    const int ntiles = gridDim.x / p.ksplit;
+    const int zsplit = logical / ntiles;
+    const int tile = logical - zsplit * ntiles;
+    const int m0 = (tile / tiles_n) * BM;
+    const int n0 = (tile % tiles_n) * BN;
 
     // The input buffer starts `lead` elements before x so that the per-lane offset of an output
     // pixel (its window's top-left tap, which may lie in the padding) is never negative.
@@ -385,17 +389,29 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     }
 
     // ---- workgroup-uniform position of the slice being issued ---------------------------------
-    const int nk = (p.Kg + BK - 1) / BK;
+    const int nk_all = (p.Kg + BK - 1) / BK;
+    const int kchunk = (nk_all + p.ksplit - 1) / p.ksplit;
+    const int k_begin = zsplit * kchunk;
+    const int k_end = k_begin + kchunk < nk_all ? k_begin + kchunk : nk_all;
+    const int nk = k_end > k_begin ? k_end - k_begin : 0;
     const bool ragged_k = (p.Kg & (BK - 1)) != 0;      // only possible for 1x1 / GEMM
-    int ki = 0;                                        // slice index
+    int ki = k_begin;                                  // slice index
     int tap = 0, ts = 0, cb = 0;                       // filter tap, its column, channel base
     unsigned tap_off = 0;                              // byte offset of the tap: (r*sH + s*sW) * 2
+    if (MODE == MODE_GATHER8 && k_begin > 0) {
+        const int per_tap = p.C / BK;
+        tap = k_begin / per_tap;
+        cb = (k_begin - tap * per_tap) * BK;
+        const int r0 = tap / p.S;
+        ts = tap - r0 * p.S;
+        tap_off = (unsigned)(r0 * p.sH + ts * p.sW) * 2u;
+    }
     const unsigned row_step = (unsigned)(p.sH - p.S * p.sW) * 2u;   // from the end of a filter row to the next
 
     auto issue = [&](int stage) {
         const unsigned sx = lds0 + (unsigned)(stage * STAGE) * 2u;
         const unsigned sw = sx + (unsigned)(BM * BK) * 2u;
-        const bool live = ki < nk;                     // slices past the end deposit zeros
+        const bool live = ki < k_end;                  // slices past the end deposit zeros
         const unsigned soff_x = MODE == MODE_1X1 ? (unsigned)ki * (BK * 2) : tap_off + (unsigned)cb * 2u;
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
@@ -452,17 +468,41 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
         issue(wr);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
+            // scheduling fences keep the reads of the next step ahead of this step's MFMAs; without
+            // them the compiler sinks the reads below the MFMAs and folds the two buffers into one
             if (ks + 1 < KS) load_frags((ks + 1) & 1, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < TNB; ++a)
 #pragma unroll
                 for (int b = 0; b < TMB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         rd = rd + 1 == STAGES ? 0 : rd + 1;
         wr = wr + 1 == STAGES ? 0 : wr + 1;
     }
     wait_loads_then_barrier<0>();                      // trailing transfers have landed; LDS is free
+
+    // ---- split-K: fp32 partial sums to this copy's slab; a second kernel reduces and finishes ------
+    if (p.ksplit > 1) {
+        float* slab = p.ws + (long long)zsplit * p.M * p.Cout;
+#pragma unroll
+        for (int a = 0; a < TNB; ++a)
+#pragma unroll
+            for (int b = 0; b < TMB; ++b) {
+                const int m = m0 + wm0 + b * 32 + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn0 + a * 32 + 8 * g + 4 * lh;
+                    if (m < p.M && n < p.Cout) {
+                        float4 v = make_float4(acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]);
+                        *(float4*)(slab + (long long)m * p.Cout + n) = v;
+                    }
+                }
+            }
+        return;
+    }
 
     // ---- epilogue (same as the first kernel's staged path) --------------------------------------
     // ReLU / ReLU6 / none are one clamp with workgroup-uniform bounds; GELU is a separate instantiation
@@ -513,9 +553,45 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     }
 }
 
+// Second pass of a split-K launch: y = act(sum_z slab_z + bias (+ res)), 8 channels per thread,
+// slabs summed in a fixed order so that results do not depend on scheduling.
+__global__ void __launch_bounds__(256) splitk_finish_kernel(const ConvParams p) {
+    if (p.hp) __builtin_amdgcn_s_setprio(3);
+    const int c8n = p.Cout >> 3;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long long)p.M * c8n) return;
+    const int m = (int)(i / c8n), n = (int)(i - (long long)m * c8n) * 8;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = p.bias ? p.bias[n + j] : 0.f;
+    const long long slab = (long long)p.M * p.Cout;
+    const float* src = p.ws + (long long)m * p.Cout + n;
+    for (int z = 0; z < p.ksplit; ++z) {
+        const float4 lo = *(const float4*)(src + z * slab), hi = *(const float4*)(src + z * slab + 4);
+        v[0] += lo.x; v[1] += lo.y; v[2] += lo.z; v[3] += lo.w; v[4] += hi.x; v[5] += hi.y; v[6] += hi.z; v[7] += hi.w;
+    }
+    if (p.res) {
+        const half8 r = *(const half8*)(p.res + (long long)m * p.ldy + n);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] += (float)r[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = apply_act(v[j], p.act);
+    if (p.out_f32) {
+        float* dst = (float*)p.y + (long long)m * p.ldy + n;
+        *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+        half8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (half_t)v[j];
+        *(half8*)((half_t*)p.y + (long long)m * p.ldy + n) = o;
+    }
+}
+
 template <int BM, int BN, int BK, int WGM, int STAGES>
 static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
-    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN);
+    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN) * p.ksplit;
     if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
     constexpr unsigned ring = STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
     constexpr unsigned lds = ring > ctile ? ring : ctile;    // the epilogue parks the output tile in the same LDS
@@ -535,6 +611,10 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_1X1, STAGES, false>);
     else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_GATHER8, STAGES, false>);
     if (rc) return rc;
+    if (p.ksplit > 1) {
+        const long long n8 = (long long)p.M * (p.Cout / 8);
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
     return 0;
@@ -578,18 +658,38 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
     p.x_elems = dense ? (long long)p.M * p.sW : (long long)(p.M / p.PQ) * p.sN;
     const long long lead = (long long)p.pad_h * p.sH + (long long)p.pad_w * p.sW;
     const bool small = (p.x_elems + lead) * 2 <= 0x7fffffffLL && (long long)p.Cout * p.ldw * 2 <= 0x7fffffffLL;
+    p.ksplit = 1;
     const bool regular = mode == MODE_1X1 || (mode == MODE_GATHER8 && p.C % 32 == 0 && p.R * p.S <= 32 && p.act != ACT_GELU);
+    // Few output tiles and a long reduction (small batches, late layers): one workgroup per tile
+    // would leave most CUs idle behind a serial chain of slices.  Split the reduction over
+    // ksplit workgroups per tile, each writing an fp32 slab, and reduce in a second launch.
+    const bool split_ok = regular && small && p.ws && p.Cout % 8 == 0 && p.ldy % 8 == 0 &&
+                          (reinterpret_cast<uintptr_t>(p.ws) & 15) == 0;
+    if (split_ok) {
+        const long long t = tiles(64, 64);
+        const int nk = (p.Kg + 31) / 32;
+        if (t <= 128 && nk >= 8) {
+            long long ks = (320 + t - 1) / t;
+            if (ks > nk / 4) ks = nk / 4;
+            if (ks > 32) ks = 32;
+            while (ks > 1 && ks * (long long)p.M * p.Cout * 4 > (long long)p.ws_bytes) --ks;
+            if (ks > 1) {
+                p.ksplit = (int)ks;
+                return launch_dma_tile<64, 64, 32, 2, 3>(p, mode, stream);
+            }
+        }
+    }
     if (staged && regular && small) {
         // Tile choice, from sweeps over the served networks' layer shapes on MI355X:
         //  - deep reductions (K >= 512) with at least 128 output channels are limited by how fast
         //    operands reach the CU: the 128x128 tile halves the bytes per flop and 64-wide slices
-        //    halve the barriers; a third stage is affordable when there are at most two tiles per CU;
+        //    halve the barriers; a third stage (one workgroup per CU) pays only when there is at most one tile per CU anyway;
         //  - shallow reductions stream activations: the 128x64 tile with few stages keeps the LDS
         //    footprint small, i.e. more workgroups in flight per CU to cover memory latency.
         const bool bk64 = mode == MODE_1X1 ? p.Kg % 64 == 0 : p.C % 64 == 0;
         const long long t128 = tiles(128, 128), t64 = tiles(128, 64);
         if (p.Kg >= 512 && p.Cout >= 128 && t128 >= 192) {
-            if (bk64) return t128 <= 512 ? launch_dma_tile<128, 128, 64, 2, 3>(p, mode, stream)
+            if (bk64) return t128 <= 256 ? launch_dma_tile<128, 128, 64, 2, 3>(p, mode, stream)
                                          : launch_dma_tile<128, 128, 64, 2, 2>(p, mode, stream);
             return launch_dma_tile<128, 128, 32, 2, 3>(p, mode, stream);
         }

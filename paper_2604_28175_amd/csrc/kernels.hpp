@@ -3,6 +3,7 @@
 // negative status (see strait.h) instead of launching when they do not hold.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace strait {
@@ -36,6 +37,9 @@ struct ConvParams {
     int out_f32;
     int hp;                  // raise wave priority (high-priority batch)
     long long x_elems;       // extent of x in elements; filled in by launch_conv
+    float* ws;               // optional split-K workspace (16-byte aligned) and its size in bytes
+    size_t ws_bytes;
+    int ksplit;              // filled in by launch_conv
 };
 
 int launch_conv(const ConvParams& p, hipStream_t stream);

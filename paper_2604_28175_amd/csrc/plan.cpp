@@ -631,6 +631,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 p.sN = op.sN; p.sH = op.sH; p.sW = op.sW;
                 p.Kg = op.vR * op.vS * op.vC; p.ldw = op.ldw;
                 p.Cout = op.K; p.ldy = op.K; p.act = op.act; p.out_f32 = op.out_f32; p.hp = hp;
+                p.ws = in.splitk_ws; p.ws_bytes = SPLITK_WS_BYTES;
                 rc = launch_conv(p, stream);
                 break;
             }

@@ -58,11 +58,14 @@ struct Instance {
     void* dev_in = nullptr;
     void* dev_out = nullptr;
     int32_t* dev_valid = nullptr;
+    float* splitk_ws = nullptr;        // fp32 slabs of split-K convolutions (small batches)
     std::vector<void*> bufs;
     hipEvent_t ev_h2d0 = nullptr, ev_h2d1 = nullptr, ev_k0 = nullptr, ev_k1 = nullptr, ev_done = nullptr;
     std::vector<hipEvent_t> layer_ev;
     bool busy = false;
 };
+
+constexpr size_t SPLITK_WS_BYTES = 16u << 20;
 
 struct Context;
 
