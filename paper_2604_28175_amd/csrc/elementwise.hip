@@ -87,64 +87,81 @@ int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, in
 
 // ------------------------------------------------------------------------------------------
 // depthwise 3x3, pad 1, stride 1 or 2, fused bias + activation.
-// A thread owns 8 channels (16 bytes) of TW consecutive output pixels of one output row and
-// slides the 3-column window along it, so every input vector is loaded once per thread; lanes of
-// a wavefront cover consecutive channel groups, i.e. contiguous memory.
+// A thread owns 8 channels (16 bytes) of TW consecutive output pixels of one output row.  For each
+// of the three input rows it loads the (TW-1)*stride+3 input vectors the strip touches once and
+// feeds all TW outputs from registers, so a strip of 4 costs 18 (stride 1) or 27 (stride 2) loads
+// instead of 36, and the index arithmetic is paid once per strip.  Lanes of a wavefront cover
+// consecutive channel groups, i.e. contiguous memory.  fp16 operands, fp32 accumulation.
 template <int STRIDE, int TW>
 __global__ void __launch_bounds__(256) dwconv3x3_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
                                                          const half_t* __restrict__ w, const float* __restrict__ bias,
                                                          int act, half_t* __restrict__ y, int P, int Q, int hp) {
     if (hp) __builtin_amdgcn_s_setprio(3);
-    const int C8 = C >> 3;
-    const int QT = (Q + TW - 1) / TW;
-    const long long total = (long long)N * P * QT * C8;
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    constexpr int NV = (TW - 1) * STRIDE + 3;
+    const unsigned C8 = (unsigned)C >> 3;
+    const unsigned QT = (unsigned)(Q + TW - 1) / TW;
+    const unsigned long long total = (unsigned long long)N * P * QT * C8;
+    const unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const int c8 = (int)(i % C8);
-    long long t = i / C8;
-    const int qt = (int)(t % QT); t /= QT;
-    const int pp = (int)(t % P);
-    const int n = (int)(t / P);
-    const int c = c8 * 8;
+    const unsigned c8 = (unsigned)(i % C8);
+    unsigned t = (unsigned)(i / C8);
+    const unsigned qt = t % QT; t /= QT;
+    const unsigned pp = t % (unsigned)P;
+    const unsigned n = t / (unsigned)P;
+    const int c = (int)c8 * 8;
 
-    float wv[9][8];
+    half8 wv[9];
 #pragma unroll
-    for (int k = 0; k < 9; ++k) {
-        const half8 h = *(const half8*)(w + (long long)k * C + c);
+    for (int k = 0; k < 9; ++k) wv[k] = *(const half8*)(w + (long long)k * C + c);
+    float acc[TW][8];
+    {
+        float bv[8];
+        if (bias) {
+            const float4 b0 = *(const float4*)(bias + c), b1 = *(const float4*)(bias + c + 4);
+            bv[0] = b0.x; bv[1] = b0.y; bv[2] = b0.z; bv[3] = b0.w; bv[4] = b1.x; bv[5] = b1.y; bv[6] = b1.z; bv[7] = b1.w;
+        } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) wv[k][j] = (float)h[j];
+            for (int j = 0; j < 8; ++j) bv[j] = 0.f;
+        }
+#pragma unroll
+        for (int tq = 0; tq < TW; ++tq)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[tq][j] = bv[j];
     }
-    float bv[8];
+    const int q0 = (int)qt * TW;
+    const int iw0 = q0 * STRIDE - 1;
+    const half_t* xin = x + (long long)n * H * W * C + c;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) bv[j] = bias ? bias[c + j] : 0.f;
-
-    const int q0 = qt * TW;
-    const int ih0 = pp * STRIDE - 1;
+    for (int r = 0; r < 3; ++r) {
+        const int ih = (int)pp * STRIDE - 1 + r;
+        if ((unsigned)ih >= (unsigned)H) continue;
+        const half_t* row = xin + (long long)ih * W * C;
+        half8 xv[NV];
 #pragma unroll
-    for (int tq = 0; tq < TW; ++tq) {
-        const int q = q0 + tq;
-        if (q >= Q) break;
-        float acc[8];
+        for (int k = 0; k < NV; ++k) {
+            const int iw = iw0 + k;
+            if ((unsigned)iw < (unsigned)W) xv[k] = *(const half8*)(row + (long long)iw * C);
+            else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = bv[j];
-        const int iw0 = q * STRIDE - 1;
-#pragma unroll
-        for (int r = 0; r < 3; ++r) {
-            const int ih = ih0 + r;
-            if ((unsigned)ih >= (unsigned)H) continue;
-#pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                const int iw = iw0 + s;
-                if ((unsigned)iw >= (unsigned)W) continue;
-                const half8 xv = *(const half8*)(x + (((long long)n * H + ih) * W + iw) * C + c);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j] += (float)xv[j] * wv[r * 3 + s][j];
+                for (int j = 0; j < 8; ++j) xv[k][j] = (half_t)0;
             }
         }
-        half8 o;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (half_t)act_f(acc[j], act);
-        *(half8*)(y + (((long long)n * P + pp) * Q + q) * C + c) = o;
+        for (int tq = 0; tq < TW; ++tq)
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[tq][j] += (float)xv[tq * STRIDE + s][j] * (float)wv[r * 3 + s][j];
+    }
+    half_t* yout = y + (((long long)n * P + pp) * Q + q0) * C + c;
+#pragma unroll
+    for (int tq = 0; tq < TW; ++tq) {
+        if (q0 + tq < Q) {
+            half8 o;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = (half_t)act_f(acc[tq][j], act);
+            *(half8*)(yout + (long long)tq * C) = o;
+        }
     }
 }
 
@@ -153,11 +170,13 @@ int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* 
     if (!x || !w_rsc || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || (stride != 1 && stride != 2)) {
         set_error("dwconv3x3: needs C %% 8 == 0 and stride 1 or 2"); return -5;
     }
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w_rsc) | reinterpret_cast<uintptr_t>(y) |
+         reinterpret_cast<uintptr_t>(bias)) & 15) { set_error("dwconv3x3: pointers must be 16-byte aligned"); return -1; }
     const int P = (H + 2 - 3) / stride + 1, Q = (W + 2 - 3) / stride + 1;
-    constexpr int TW = 2;
+    constexpr int TW = 4;
     const long long total = (long long)N * P * ((Q + TW - 1) / TW) * (C / 8);
     const long long blocks = (total + 255) / 256;
-    if (blocks > 0x7fffffffLL) { set_error("dwconv3x3: grid too large"); return -5; }
+    if (blocks > 0x7fffffffLL || (long long)N * P * ((Q + TW - 1) / TW) > 0xffffffffLL) { set_error("dwconv3x3: grid too large"); return -5; }
     if (stride == 1)
         hipLaunchKernelGGL((dwconv3x3_kernel<1, TW>), dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, P, Q, hp);
     else
