@@ -146,7 +146,7 @@ def main() -> int:
                    "batch": B, "priority": "high"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "conv_igemm_kernel (all tile shapes), 54 launches per step",
+                     "kernel": "conv_igemm_dma_kernel / conv_igemm_kernel (all tile shapes), 54 convolution launches per step",
                      "flops_per_step": conv_flops, "kernel_ms_per_step": round(conv_ms, 4),
                      "other_kernels_ms_per_step": round(other_ms, 4),
                      "layerwise_roofline_ms": round(t_roof * 1e3, 4),

@@ -232,31 +232,45 @@ int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, 
 
 // ------------------------------------------------------------------------------------------
 // global average pooling: [N][HW][C] -> [N][C], fp32 sum / HW, rounded once to fp16.
+// A workgroup covers 32 channel groups (256 channels) of one image; its 8 wavefront-halves each
+// sum every 8th position and the partial sums meet in LDS, so the loads of one image are spread
+// over 8 independent chains instead of one serial walk over HW.
 __global__ void __launch_bounds__(256) gap_kernel(const half_t* __restrict__ x, int N, int HW, int C,
                                                    half_t* __restrict__ y, int hp) {
+    __shared__ float part[8][32][8];
     if (hp) __builtin_amdgcn_s_setprio(3);
     const int C8 = C >> 3;
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long long)N * C8) return;
-    const int c8 = (int)(i % C8), n = (int)(i / C8);
+    const int g = threadIdx.x & 31, part_id = threadIdx.x >> 5;
+    const int c8 = blockIdx.x * 32 + g, n = blockIdx.y;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const half_t* src = x + (long long)n * HW * C + c8 * 8;
-    for (int k = 0; k < HW; ++k) {
-        const half8 v = *(const half8*)(src + (long long)k * C);
+    if (c8 < C8) {
+        const half_t* src = x + (long long)n * HW * C + c8 * 8;
+        for (int k = part_id; k < HW; k += 8) {
+            const half8 v = *(const half8*)(src + (long long)k * C);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += (float)v[j];
+            for (int j = 0; j < 8; ++j) acc[j] += (float)v[j];
+        }
     }
-    const float inv = 1.f / (float)HW;
-    half8 o;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (half_t)(acc[j] * inv);
-    *(half8*)(y + (long long)n * C + c8 * 8) = o;
+    for (int j = 0; j < 8; ++j) part[part_id][g][j] = acc[j];
+    __syncthreads();
+    if (part_id == 0 && c8 < C8) {
+        const float inv = 1.f / (float)HW;
+        half8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float s = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) s += part[q][g][j];
+            o[j] = (half_t)(s * inv);
+        }
+        *(half8*)(y + (long long)n * C + c8 * 8) = o;
+    }
 }
 
 int launch_global_avgpool(const half_t* x, int N, int HW, int C, half_t* y, int hp, hipStream_t stream) {
-    if (!x || !y || N <= 0 || HW <= 0 || C <= 0 || C % 8 != 0) { set_error("avgpool: needs C %% 8 == 0"); return -5; }
-    const long long blocks = ((long long)N * (C / 8) + 255) / 256;
-    hipLaunchKernelGGL(gap_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, HW, C, y, hp);
+    if (!x || !y || N <= 0 || HW <= 0 || C <= 0 || C % 8 != 0 || N > 65535) { set_error("avgpool: needs C %% 8 == 0 and N <= 65535"); return -5; }
+    hipLaunchKernelGGL(gap_kernel, dim3((unsigned)((C / 8 + 31) / 32), (unsigned)N), dim3(256), 0, stream, x, N, HW, C, y, hp);
     STRAIT_CHECK_LAUNCH("avgpool");
     return 0;
 }
@@ -274,7 +288,9 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// softmax + top-1: one wavefront per row of fp32 logits.
+// softmax + top-1: one wavefront per row of fp32 logits; rows of up to 64 * PER elements are read
+// once and kept in registers (PER = 16 covers the 1000-class heads), longer rows are re-read.
+template <int PER>
 __global__ void __launch_bounds__(256) softmax_top1_kernel(const float* __restrict__ logits, int rows, int n,
                                                             float* __restrict__ probs, int32_t* __restrict__ top1, int hp) {
     if (hp) __builtin_amdgcn_s_setprio(3);
@@ -282,11 +298,21 @@ __global__ void __launch_bounds__(256) softmax_top1_kernel(const float* __restri
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const float* src = logits + (long long)row * n;
+    float v[PER > 0 ? PER : 1];
     float mx = -INFINITY;
     int mi = 0x7fffffff;
-    for (int i = lane; i < n; i += 64) {
-        const float v = src[i];
-        if (v > mx) { mx = v; mi = i; }       // ascending i: keeps the lowest index on ties
+    if (PER > 0) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = lane + k * 64;
+            v[k] = i < n ? src[i] : -INFINITY;
+            if (v[k] > mx) { mx = v[k]; mi = i; }           // ascending i: keeps the lowest index on ties
+        }
+    } else {
+        for (int i = lane; i < n; i += 64) {
+            const float t = src[i];
+            if (t > mx) { mx = t; mi = i; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -295,17 +321,33 @@ __global__ void __launch_bounds__(256) softmax_top1_kernel(const float* __restri
         if (ov > mx || (ov == mx && oi < mi)) { mx = ov; mi = oi; }
     }
     float sum = 0.f;
-    for (int i = lane; i < n; i += 64) sum += __expf(src[i] - mx);
+    if (PER > 0) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) { v[k] = __expf(v[k] - mx); sum += v[k]; }    // exp(-inf) = 0 past the row end
+    } else {
+        for (int i = lane; i < n; i += 64) sum += __expf(src[i] - mx);
+    }
     sum = wave_sum(sum);
     const float inv = 1.f / sum;
     float* dst = probs + (long long)row * n;
-    for (int i = lane; i < n; i += 64) dst[i] = __expf(src[i] - mx) * inv;
+    if (PER > 0) {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = lane + k * 64;
+            if (i < n) dst[i] = v[k] * inv;
+        }
+    } else {
+        for (int i = lane; i < n; i += 64) dst[i] = __expf(src[i] - mx) * inv;
+    }
     if (lane == 0) top1[row] = mi;
 }
 
 int launch_softmax_top1(const float* logits, int rows, int n, float* probs, int32_t* top1, int hp, hipStream_t stream) {
     if (!logits || !probs || !top1 || rows <= 0 || n <= 0) { set_error("softmax: invalid shape"); return -5; }
-    hipLaunchKernelGGL(softmax_top1_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, logits, rows, n, probs, top1, hp);
+    const dim3 grid((rows + 3) / 4), block(256);
+    if (n <= 128) hipLaunchKernelGGL(softmax_top1_kernel<2>, grid, block, 0, stream, logits, rows, n, probs, top1, hp);
+    else if (n <= 1024) hipLaunchKernelGGL(softmax_top1_kernel<16>, grid, block, 0, stream, logits, rows, n, probs, top1, hp);
+    else hipLaunchKernelGGL(softmax_top1_kernel<0>, grid, block, 0, stream, logits, rows, n, probs, top1, hp);
     STRAIT_CHECK_LAUNCH("softmax");
     return 0;
 }
