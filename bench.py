@@ -7,10 +7,11 @@ input already sits in device memory.  Prints ONE JSON line:
 
   value         images/s over the K timed steps
   roofline      the implicit-GEMM convolution kernel (53 convolutions + FC per step): algorithmic
-                flops of those launches divided by their summed device time, measured with a HIP
-                event pair around every layer on the stream the kernels run on, during a second
-                pass of K steps (the event pairs cost a few percent, so they are kept out of the
-                pass that `value` is taken from)
+                flops of those launches divided by their device time.  Device time = HIP events
+                around the K timed steps on the launch stream, minus the non-convolution kernels'
+                time; a second pass of K steps with an event pair around every layer supplies the
+                latter and the per-layer split (event pairs open gaps between launches, so they
+                are kept out of the pass `value` is taken from)
   cpu_baseline  the CPU oracle's ResNet-50 forward timed on this host on a bounded sample
   by_batch      images/s at the other batch sizes of the workload (1, 8, 32), shorter runs
 """
@@ -100,17 +101,22 @@ def main() -> int:
     model.sync(0, prio)
     torch.cuda.synchronize()
 
+    stream = ctx.hp_streams[0]                    # the stream strait_run launches on at high priority
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
     def timed(m, batch, steps, warmup):
         for _ in range(warmup):
             m.run(0, prio, batch)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        ev0.record(stream)
         for _ in range(steps):
             m.run(0, prio, batch)
+        ev1.record(stream)
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        return time.perf_counter() - t0, ev0.elapsed_time(ev1)
 
-    dt = timed(model, B, K, W)
+    dt, dev_ms = timed(model, B, K, W)
     value = K * B / dt
 
     # ---- roofline of the dominant kernel (implicit-GEMM convolution), per-layer event pairs
@@ -121,6 +127,13 @@ def main() -> int:
     ms /= K
     conv = [i for i, l in enumerate(layers) if l.kind == 0]
     conv_flops = sum(2.0 * layers[i].macs_per_sample * B for i in conv)
+    # Device time of the convolution launches per step: the timed region's own device time (one HIP
+    # event before and after the K steps, on the launch stream) minus the other kernels' time.  The
+    # per-layer event pairs of the second pass only apportion it: an event pair around every launch
+    # opens a gap of a few microseconds per launch, which would otherwise be booked to the kernels.
+    other_ms = float(ms.sum()) - float(sum(ms[i] for i in conv))
+    scale = (dev_ms / K - other_ms) / float(sum(ms[i] for i in conv))
+    ms = np.array([ms[i] * scale if i in set(conv) else ms[i] for i in range(len(ms))])
     conv_ms = float(sum(ms[i] for i in conv))
     achieved = conv_flops / (conv_ms * 1e-3) / 1e12
     # per-class view: MFMA-bound layers (arithmetic intensity above the machine balance) vs the rest
@@ -136,7 +149,6 @@ def main() -> int:
         cls[key][1] += by
         cls[key][2] += ms[i]
         t_roof += max(fl / (MFMA_F16_PEAK_TFLOPS * 1e12), by / (HBM_PEAK_GBS * 1e9))
-    other_ms = float(ms.sum()) - conv_ms
     out = {
         "metric": "ResNet-50 fp16 images/s by batch; high-prio p99 latency solo vs co-located",
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -164,7 +176,7 @@ def main() -> int:
             xb = synth.default_image_batch(md, b, seed + b)
             model.copy_in(0, prio, xb)
             model.sync(0, prio)
-            d = timed(model, b, max(20, K), max(5, W))
+            d, _ = timed(model, b, max(20, K), max(5, W))
             by[str(b)] = round(max(20, K) * b / d, 1)
         out["by_batch"] = by
 

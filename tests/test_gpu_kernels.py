@@ -182,3 +182,44 @@ def test_launchers_reject_bad_shapes(S):
         S.k_attention(dev(S, np.zeros((1, 48, 192), np.float16)), dev(S, np.array([48], np.int32)), 1)   # S % 32 != 0
     with pytest.raises(S.StraitError):
         S.k_layernorm(dev(S, np.zeros((2, 12), np.float16)), dev(S, np.ones(12, np.float32)), dev(S, np.zeros(12, np.float32)), 1e-5)
+
+
+SPLITK_CASES = [
+    # N, H, W, C, K, R, stride, pad, act, residual, out_f32   (few output tiles + long reduction: split-K path)
+    (1, 7, 7, 512, 512, 3, 1, 1, 1, True, False),       # 49 pixels, K = 4608, residual + ReLU in the finishing kernel
+    (2, 14, 14, 256, 256, 3, 2, 1, 1, False, False),    # strided 3x3, slices start in the middle of the tap sequence
+    (1, 7, 7, 1024, 512, 1, 1, 0, 2, False, False),     # 1x1, ReLU6
+    (8, 1, 1, 2048, 1000, 1, 1, 0, 0, False, True),     # classifier head: fp32 logits out of the finishing kernel
+    (3, 9, 11, 64, 72, 3, 1, 1, 0, False, False),       # ragged M and N tiles, uneven split of the 18 slices
+]
+
+
+@pytest.mark.parametrize("case", SPLITK_CASES, ids=lambda c: "x".join(map(str, c[:8])))
+def test_conv2d_split_k(S, case):
+    N, H, W, C, K, Rk, stride, pad, act, use_res, out_f32 = case
+    x = f16(R.standard_normal((N, H, W, C)))
+    w = f16(R.standard_normal((K, C, Rk, Rk)) * (2.0 / (C * Rk * Rk)) ** 0.5)
+    b = R.standard_normal(K).astype(np.float32)
+    ref = ops.conv2d(x, w, b, stride, pad)
+    res = f16(R.standard_normal(ref.shape)) if use_res else None
+    if use_res:
+        ref = ref + res.astype(np.float64)
+    ref = act_ref(ref, act)
+    w_krsc = np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))
+    args = (dev(S, x), dev(S, w_krsc), dev(S, b), stride, pad, act, None if res is None else dev(S, res), out_f32)
+    y1 = S.k_conv2d(*args).float().cpu().numpy()
+    check_kernel(y1, ref, f"split-K conv {case}")
+    # slabs are reduced in a fixed order: a second launch gives the same bits
+    y2 = S.k_conv2d(*args).float().cpu().numpy()
+    assert np.array_equal(y1, y2)
+
+
+def test_gemm_gelu_and_ragged_k(S):
+    """GELU epilogue of the pipelined kernel and a reduction that is not a multiple of the slice."""
+    for (M, N, K, act) in [(512, 768, 776, 3), (1000, 256, 40, 0), (4096, 3072, 768, 3)]:
+        x = f16(R.standard_normal((M, K)))
+        w = f16(R.standard_normal((N, K)) * K ** -0.5)
+        b = (R.standard_normal(N) * 0.1).astype(np.float32)
+        ref = act_ref(ops.linear(x, w, b), act)
+        y = S.k_gemm(dev(S, x), dev(S, w), dev(S, b), act)
+        check_kernel(y.float().cpu().numpy(), ref, f"gemm {M}x{N}x{K} act {act}")
