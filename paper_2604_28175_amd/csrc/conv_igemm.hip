@@ -28,10 +28,21 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 enum { MODE_1X1 = 0, MODE_GATHER8 = 1, MODE_SCALAR = 2 };
 
+// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7, far below
+// the 2^-11 resolution of the fp16 result): 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1/(1 + p|x|).
+__device__ __forceinline__ float fast_erf(float x) {
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * ax);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float r = 1.f - poly * __expf(-ax * ax);
+    return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.f + fast_erf(v * 0.70710678118654752440f)); }
+
 __device__ __forceinline__ float apply_act(float v, int act) {
     if (act == ACT_RELU) return fmaxf(v, 0.f);
     if (act == ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
-    if (act == ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    if (act == ACT_GELU) return gelu_f(v);
     return v;
 }
 
@@ -307,15 +318,15 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BK, int WGM, int MODE, int STAGES, bool GELU>
-__global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p) {
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU>
+__global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const ConvParams p) {
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
     constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
-    constexpr int WGN = 4 / WGM;                       // the 4 waves form a WGM x WGN grid over the tile
+    constexpr int NW = WGM * WGN, NT = 64 * NW;        // the waves form a WGM x WGN grid over the tile
     constexpr int TM = BM / WGM, TN = BN / WGN;
     constexpr int TMB = TM / 32, TNB = TN / 32;
-    constexpr int XI = BM / (4 * RPI), WI = BN / (4 * RPI);   // transfers per wave per slice
+    constexpr int XI = BM / (NW * RPI), WI = BN / (NW * RPI); // transfers per wave per slice
     static_assert((BK == 32 || BK == 64) && TM % 32 == 0 && TN % 32 == 0 && XI >= 1 && WI >= 1, "unsupported tile");
     constexpr int STAGE = (BM + BN) * BK;              // halfs per stage
     constexpr int LDC = BN + 8;
@@ -358,7 +369,7 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     unsigned xoff[XI], tapmask[XI];
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
-        const int m = m0 + (j * 4 + wave) * RPI + rsub;
+        const int m = m0 + (j * NW + wave) * RPI + rsub;
         xoff[j] = OOB_OFFSET;
         tapmask[j] = 0xffffffffu;
         if (m < p.M) {
@@ -384,7 +395,7 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     unsigned woff[WI];
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
-        const int n = n0 + (j * 4 + wave) * RPI + rsub;
+        const int n = n0 + (j * NW + wave) * RPI + rsub;
         woff[j] = n < p.Cout ? (unsigned)(((long long)n * p.ldw + cl * 8) * 2) : OOB_OFFSET;
     }
 
@@ -419,11 +430,11 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
             if (MODE == MODE_GATHER8) v = ((tapmask[j] >> tap) & 1u) ? v : OOB_OFFSET;
             if (MODE == MODE_1X1 && ragged_k) v = (ki * BK + cl * 8 < p.Kg) ? v : OOB_OFFSET;
             if (!live) v = OOB_OFFSET;
-            dma16(xrsrc, v, live ? soff_x : 0u, sx + (unsigned)((j * 4 + wave) * 1024));
+            dma16(xrsrc, v, live ? soff_x : 0u, sx + (unsigned)((j * NW + wave) * 1024));
         }
 #pragma unroll
         for (int j = 0; j < WI; ++j)
-            dma16(wrsrc, live ? woff[j] : OOB_OFFSET, live ? (unsigned)ki * (BK * 2) : 0u, sw + (unsigned)((j * 4 + wave) * 1024));
+            dma16(wrsrc, live ? woff[j] : OOB_OFFSET, live ? (unsigned)ki * (BK * 2) : 0u, sw + (unsigned)((j * NW + wave) * 1024));
         ++ki;
         if (MODE == MODE_GATHER8) {
             cb += BK;
@@ -511,7 +522,7 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     const float lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? 0.f : -INFINITY;
     const float hi = p.act == ACT_RELU6 ? 6.f : INFINITY;
     auto activate = [&](float v) {
-        if (GELU) v = 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+        if (GELU) v = gelu_f(v);
         return fminf(fmaxf(v, lo), hi);
     };
 #pragma unroll
@@ -537,8 +548,8 @@ __global__ void __launch_bounds__(256) conv_igemm_dma_kernel(const ConvParams p)
     __syncthreads();
     constexpr int CPR = BN / 8;
 #pragma unroll
-    for (int i = 0; i < BM * CPR / 256; ++i) {
-        const int id = tid + i * 256;
+    for (int i = 0; i < BM * CPR / NT; ++i) {
+        const int id = tid + i * NT;
         const int row = id / CPR, c8 = id - row * CPR;
         const int m = m0 + row, n = n0 + c8 * 8;
         if (m < p.M && n < p.Cout) {
@@ -589,13 +600,13 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(const ConvParams p) 
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int STAGES>
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN) * p.ksplit;
     if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
     constexpr unsigned ring = STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
     constexpr unsigned lds = ring > ctile ? ring : ctile;    // the epilogue parks the output tile in the same LDS
-    dim3 grid((unsigned)tiles), block(256);
+    dim3 grid((unsigned)tiles), block(64 * WGM * WGN);
     auto go = [&](auto kernel) -> int {
         static bool configured = false;                 // one flag per instantiation
         if (!configured && lds > 48 * 1024) {
@@ -607,9 +618,9 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
         return 0;
     };
     int rc;
-    if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_1X1, STAGES, true>);
-    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_1X1, STAGES, false>);
-    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, MODE_GATHER8, STAGES, false>);
+    if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, true>);
+    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false>);
+    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false>);
     if (rc) return rc;
     if (p.ksplit > 1) {
         const long long n8 = (long long)p.M * (p.Cout / 8);
@@ -675,7 +686,7 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
             while (ks > 1 && ks * (long long)p.M * p.Cout * 4 > (long long)p.ws_bytes) --ks;
             if (ks > 1) {
                 p.ksplit = (int)ks;
-                return launch_dma_tile<64, 64, 32, 2, 3>(p, mode, stream);
+                return launch_dma_tile<64, 64, 32, 2, 2, 3>(p, mode, stream);
             }
         }
     }
@@ -688,14 +699,16 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         //    footprint small, i.e. more workgroups in flight per CU to cover memory latency.
         const bool bk64 = mode == MODE_1X1 ? p.Kg % 64 == 0 : p.C % 64 == 0;
         const long long t128 = tiles(128, 128), t64 = tiles(128, 64);
+        if (p.Kg >= 512 && p.Cout >= 256 && tiles(256, 128) >= 512)      // plenty of tiles: 8 waves on 256x128
+            return launch_dma_tile<256, 128, 32, 2, 4, 3>(p, mode, stream);
         if (p.Kg >= 512 && p.Cout >= 128 && t128 >= 192) {
-            if (bk64) return t128 <= 256 ? launch_dma_tile<128, 128, 64, 2, 3>(p, mode, stream)
-                                         : launch_dma_tile<128, 128, 64, 2, 2>(p, mode, stream);
-            return launch_dma_tile<128, 128, 32, 2, 3>(p, mode, stream);
+            if (bk64) return t128 <= 256 ? launch_dma_tile<128, 128, 64, 2, 2, 3>(p, mode, stream)
+                                         : launch_dma_tile<128, 128, 64, 2, 2, 2>(p, mode, stream);
+            return launch_dma_tile<128, 128, 32, 2, 2, 3>(p, mode, stream);
         }
-        if (t64 >= 256) return p.Kg >= 288 ? launch_dma_tile<128, 64, 32, 2, 3>(p, mode, stream)
-                                           : launch_dma_tile<128, 64, 32, 2, 2>(p, mode, stream);
-        return launch_dma_tile<64, 64, 32, 2, 2>(p, mode, stream);
+        if (t64 >= 256) return p.Kg >= 288 ? launch_dma_tile<128, 64, 32, 2, 2, 3>(p, mode, stream)
+                                           : launch_dma_tile<128, 64, 32, 2, 2, 2>(p, mode, stream);
+        return launch_dma_tile<64, 64, 32, 2, 2, 2>(p, mode, stream);
     }
     if (p.Cout > 64 && tiles(128, 128) >= 512) return launch_tile<128, 128>(p, mode, staged, stream);
     if (tiles(128, 64) >= 512) return launch_tile<128, 64>(p, mode, staged, stream);
