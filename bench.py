@@ -33,6 +33,20 @@ MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic(batch):
+    """HBM bytes per step of the convolution launches from the committed hardware-counter runs, or None
+    when the kernel source has changed since they were taken (or the workload differs)."""
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic_conv_igemm_resnet50_b128.json")))
+        src = open(os.path.join(ROOT, rec["kernel_source"]), "rb").read()
+    except (OSError, ValueError, KeyError):
+        return None
+    if batch != 128 or hashlib.sha256(src).hexdigest() != rec.get("kernel_source_sha256"):
+        return None
+    return rec.get("hbm_bytes_per_step")
+
+
 def colocation(ctx, md_resnet, blob_resnet, seconds):
     """High-priority ResNet-50 b8 requests, Poisson at 200/s, next to low-priority MobileNetV2 b64
     issued back to back; per-request latency solo vs co-located, with and without wave priority."""
@@ -77,6 +91,8 @@ def main() -> int:
     ap.add_argument("--no-by-batch", action="store_true")
     ap.add_argument("--colocation-seconds", type=float, default=2.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
+    ap.add_argument("--copy-calibration-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference for hardware byte counters)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images the CPU oracle is timed on (0 = twelve per thread)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -115,6 +131,13 @@ def main() -> int:
         ev1.record(stream)
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ev0.elapsed_time(ev1)
+
+    if args.copy_calibration_mb > 0:
+        src = torch.empty(args.copy_calibration_mb << 20, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     dt, dev_ms = timed(model, B, K, W)
     value = K * B / dt
@@ -157,7 +180,8 @@ def main() -> int:
         "config": {"workload": f"resnet50_v1.5 224x224 fp16 NHWC, batch {B}, BatchNorm folded, input resident in HBM",
                    "batch": B, "priority": "high"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic(B),
+                     "algorithmic_bytes_per_step": sum(float(layers[i].bytes_per_sample) * B + layers[i].weight_bytes for i in conv),
                      "kernel": "conv_igemm_dma_kernel / conv_igemm_kernel (all tile shapes), 54 convolution launches per step",
                      "flops_per_step": conv_flops, "kernel_ms_per_step": round(conv_ms, 4),
                      "other_kernels_ms_per_step": round(other_ms, 4),
