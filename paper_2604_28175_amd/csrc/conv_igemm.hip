@@ -701,6 +701,8 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         const long long t128 = tiles(128, 128), t64 = tiles(128, 64);
         if (p.Kg >= 512 && p.Cout >= 256 && tiles(256, 128) >= 512)      // plenty of tiles: 8 waves on 256x128
             return launch_dma_tile<256, 128, 32, 2, 4, 3>(p, mode, stream);
+        if (p.Kg >= 256 && p.Kg < 512 && p.Cout >= 1024 && tiles(128, 256) >= 192)   // wide outputs, medium reduction
+            return launch_dma_tile<128, 256, 32, 2, 4, 2>(p, mode, stream);
         if (p.Kg >= 512 && p.Cout >= 128 && t128 >= 192) {
             if (bk64) return t128 <= 256 ? launch_dma_tile<128, 128, 64, 2, 2, 3>(p, mode, stream)
                                          : launch_dma_tile<128, 128, 64, 2, 2, 2>(p, mode, stream);
