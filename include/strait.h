@@ -211,6 +211,28 @@ strait_status strait_k_attention(void* stream, const void* qkv, const int32_t* v
 strait_status strait_k_argmax_f16(void* stream, const void* x, int32_t rows, int32_t n, int64_t row_stride,
                                   int32_t* top1, int32_t hp);
 
+/* ---- host-to-device link model (host only; no GPU needed) -----------------------------------
+ * Section 3.2 of the paper, "Interference in data transfer": pinned transfers of concurrent
+ * batches are served first-in first-out, so
+ *     T_data = max(0, t_available - t_current)                        (Eq. 2)
+ *     t_available <- max(t_current, t_available) + t_HtoD(i,j)        (Eq. 3)
+ * and ("Online calibration") once a transfer has been timed, its measured end replaces the
+ * estimate: Eq. 3 is then carried forward from the measured end over the transfers scheduled
+ * after it.  All times are int64 nanoseconds on one clock of the caller's choice.  Thread-safe. */
+typedef struct strait_link strait_link;
+strait_status strait_link_create(strait_link** out);
+strait_status strait_link_destroy(strait_link* link);
+/* t_available as it stands (INT64_MIN before the first transfer). */
+strait_status strait_link_available(const strait_link* link, int64_t* t_available_ns);
+/* Eq. 2 for a batch that would be submitted at t_current. */
+strait_status strait_link_predict(const strait_link* link, int64_t t_current_ns, int64_t* t_data_ns);
+/* Eq. 2 (optional output) followed by Eq. 3 for a batch whose isolated transfer takes t_htod. */
+strait_status strait_link_schedule(strait_link* link, int64_t t_current_ns, int64_t t_htod_ns,
+                                   uint64_t* transfer_id, int64_t* t_data_ns);
+/* Online calibration: transfer `transfer_id` was observed to end at t_end.  E_INVALID for an id
+ * that is unknown or older than an already calibrated transfer. */
+strait_status strait_link_complete(strait_link* link, uint64_t transfer_id, int64_t t_end_ns);
+
 #ifdef __cplusplus
 }
 #endif

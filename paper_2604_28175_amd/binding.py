@@ -90,6 +90,12 @@ _SIGS = {
     "strait_k_layernorm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, C.c_float, _vp, _i32]),
     "strait_k_attention": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_argmax_f16": (_i32, [_vp, _vp, _i32, _i32, _i64, _vp, _i32]),
+    "strait_link_create": (_i32, [C.POINTER(_vp)]),
+    "strait_link_destroy": (_i32, [_vp]),
+    "strait_link_available": (_i32, [_vp, C.POINTER(_i64)]),
+    "strait_link_predict": (_i32, [_vp, _i64, C.POINTER(_i64)]),
+    "strait_link_schedule": (_i32, [_vp, _i64, _i64, C.POINTER(C.c_uint64), C.POINTER(_i64)]),
+    "strait_link_complete": (_i32, [_vp, C.c_uint64, _i64]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -348,3 +354,34 @@ def k_argmax_f16(x, n, row_stride, rows, hp=0, stream=None):
     top1 = torch.empty((rows,), dtype=torch.int32, device=x.device)
     _check(lib.strait_k_argmax_f16(_stream(stream), _dev(x), rows, n, row_stride, _dev(top1), hp))
     return top1
+
+
+class Link:
+    """strait_link: the first-in first-out model of the host-to-device link (host only)."""
+
+    def __init__(self):
+        self.handle = _vp()
+        _check(lib.strait_link_create(C.byref(self.handle)))
+
+    def available(self) -> int:
+        v = _i64()
+        _check(lib.strait_link_available(self.handle, C.byref(v)))
+        return v.value
+
+    def predict(self, t_current_ns: int) -> int:
+        v = _i64()
+        _check(lib.strait_link_predict(self.handle, t_current_ns, C.byref(v)))
+        return v.value
+
+    def schedule(self, t_current_ns: int, t_htod_ns: int):
+        tid, v = C.c_uint64(), _i64()
+        _check(lib.strait_link_schedule(self.handle, t_current_ns, t_htod_ns, C.byref(tid), C.byref(v)))
+        return tid.value, v.value
+
+    def complete(self, transfer_id: int, t_end_ns: int):
+        _check(lib.strait_link_complete(self.handle, transfer_id, t_end_ns))
+
+    def close(self):
+        if self.handle:
+            _check(lib.strait_link_destroy(self.handle))
+            self.handle = _vp()
