@@ -233,6 +233,50 @@ strait_status strait_link_schedule(strait_link* link, int64_t t_current_ns, int6
  * that is unknown or older than an already calibrated transfer. */
 strait_status strait_link_complete(strait_link* link, uint64_t transfer_id, int64_t t_end_ns);
 
+/* ---- kernel-interference predictor (host only; no GPU needed) -------------------------------
+ * Section 3.2 of the paper, "Interference in kernel execution" and "Self-adaptive model":
+ *     kernel_eff = k * b^LR(m_avg^1..n | m_self^cmp, m_self^mem) + C          (Eq. 4)
+ *     Intf       = 1 + kernel_eff * coeff_p                                    (Eq. 5)
+ *     T_kernel   = (Intf - 1) * T_kernel^isol                                  (Eq. 6)
+ * LR is a weighted sum without intercept.  The STRAIT_INTF_METRICS co-located metrics are, in
+ * order, the utilisation of: LDS/L1, L2, DRAM, matrix pipes, FMA pipes (fractions of peak);
+ * m_self^cmp is the batch's own matrix-pipe and m_self^mem its own L2 utilisation.  A batch
+ * whose m_avg is all zero (never had a neighbour) has Intf = 1 and does not train the model.
+ * coeff_p is indexed by strait_priority.  All arithmetic is fp64.  Thread-safe. */
+#define STRAIT_INTF_METRICS 5
+typedef struct strait_intf_params {
+    double k, b, C;
+    double w_avg[STRAIT_INTF_METRICS];
+    double w_self_cmp, w_self_mem;
+    double coeff_p[2];
+} strait_intf_params;
+typedef struct strait_intf strait_intf;
+/* init == NULL: conservative start (k 1, b 2, C -1, w_avg 0.5 each, w_self 0, coeff_p 1).
+ * E_INVALID if init->b < 1e-6. */
+strait_status strait_intf_create(const strait_intf_params* init, strait_intf** out);
+strait_status strait_intf_destroy(strait_intf* p);
+strait_status strait_intf_get_params(const strait_intf* p, strait_intf_params* out);
+/* Resource demand of a batch: m_out[i] = sum_j v[j][i] d[j] / sum_j d[j] over its n kernels
+ * (v row-major [n][STRAIT_INTF_METRICS], d >= 0 with a positive sum). */
+strait_status strait_intf_demand(const double* v, const double* d, int32_t n, double* m_out);
+/* Eq. 4-6 for one batch; either output may be NULL (not both). */
+strait_status strait_intf_predict(const strait_intf* p, const double* m_avg, double m_self_cmp, double m_self_mem,
+                                  int32_t priority, double t_kernel_isol, double* intf_hat, double* t_kernel);
+/* One online step for a completed batch whose measured slowdown (kernel latency over the
+ * profiled isolated latency) was intf_actual: Adam (beta1 0.7, beta2 0.9, alpha 0.0075, eps
+ * 1e-8, bias-corrected) on the Huber loss (delta 0.5) of (predicted - actual); afterwards b is
+ * kept >= 1e-6.  loss (optional) receives the loss before the step. */
+strait_status strait_intf_update(strait_intf* p, const double* m_avg, double m_self_cmp, double m_self_mem,
+                                 int32_t priority, double intf_actual, double* loss);
+/* Co-location dynamics of one GPU.  arrive: a batch of demand m[STRAIT_INTF_METRICS] starts at
+ * t; depart: it ends at t, m_avg_out receives the time-weighted average, over its life, of the
+ * summed demands of the batches that ran beside it.  Times are int64 nanoseconds, never
+ * decreasing across calls (E_INVALID otherwise, or for an unknown id). */
+strait_status strait_intf_arrive(strait_intf* p, int64_t t_ns, const double* m, uint64_t* batch_id);
+strait_status strait_intf_depart(strait_intf* p, uint64_t batch_id, int64_t t_ns, double* m_avg_out);
+/* Summed demand of the batches running now, leaving out exclude_id (0 = none). */
+strait_status strait_intf_pressure(const strait_intf* p, uint64_t exclude_id, double* m_now);
+
 #ifdef __cplusplus
 }
 #endif

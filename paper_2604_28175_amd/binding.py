@@ -60,7 +60,7 @@ class LayerInfo(C.Structure):
                 ("gemm_m_per_sample", C.c_int32), ("gemm_n", C.c_int32), ("gemm_k", C.c_int32)]
 
 
-_vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+_vp, _i32, _i64, _sz, _f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_double
 _SIGS = {
     "strait_last_error": (C.c_char_p, []),
     "strait_version": (_i32, []),
@@ -96,6 +96,15 @@ _SIGS = {
     "strait_link_predict": (_i32, [_vp, _i64, C.POINTER(_i64)]),
     "strait_link_schedule": (_i32, [_vp, _i64, _i64, C.POINTER(C.c_uint64), C.POINTER(_i64)]),
     "strait_link_complete": (_i32, [_vp, C.c_uint64, _i64]),
+    "strait_intf_create": (_i32, [_vp, C.POINTER(_vp)]),
+    "strait_intf_destroy": (_i32, [_vp]),
+    "strait_intf_get_params": (_i32, [_vp, _vp]),
+    "strait_intf_demand": (_i32, [_vp, _vp, _i32, _vp]),
+    "strait_intf_predict": (_i32, [_vp, _vp, _f64, _f64, _i32, _f64, C.POINTER(_f64), C.POINTER(_f64)]),
+    "strait_intf_update": (_i32, [_vp, _vp, _f64, _f64, _i32, _f64, C.POINTER(_f64)]),
+    "strait_intf_arrive": (_i32, [_vp, _i64, _vp, C.POINTER(C.c_uint64)]),
+    "strait_intf_depart": (_i32, [_vp, C.c_uint64, _i64, _vp]),
+    "strait_intf_pressure": (_i32, [_vp, C.c_uint64, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -384,4 +393,80 @@ class Link:
     def close(self):
         if self.handle:
             _check(lib.strait_link_destroy(self.handle))
+            self.handle = _vp()
+
+
+INTF_METRICS = 5
+
+
+class IntfParams(C.Structure):
+    """strait_intf_params."""
+    _fields_ = [("k", _f64), ("b", _f64), ("C", _f64), ("w_avg", _f64 * INTF_METRICS), ("w_self_cmp", _f64),
+                ("w_self_mem", _f64), ("coeff_p", _f64 * 2)]
+
+    def as_vector(self) -> np.ndarray:
+        return np.array([self.k, self.b, self.C, *self.w_avg, self.w_self_cmp, self.w_self_mem, *self.coeff_p])
+
+    @classmethod
+    def from_vector(cls, v):
+        v = [float(x) for x in v]
+        return cls(v[0], v[1], v[2], (_f64 * INTF_METRICS)(*v[3:8]), v[8], v[9], (_f64 * 2)(*v[10:12]))
+
+
+def _f64v(a, n=INTF_METRICS):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if a.size != n:
+        raise ValueError(f"expected {n} values")
+    return a
+
+
+def intf_demand(v, d) -> np.ndarray:
+    d = np.ascontiguousarray(d, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64).reshape(d.size, INTF_METRICS)
+    out = np.zeros(INTF_METRICS)
+    _check(lib.strait_intf_demand(_np_ptr(v), _np_ptr(d), d.size, _np_ptr(out)))
+    return out
+
+
+class Interference:
+    """strait_intf: the kernel-interference predictor with its online update and co-location tracker (host only)."""
+
+    def __init__(self, params=None):
+        self.handle = _vp()
+        init = None if params is None else C.byref(IntfParams.from_vector(params))
+        _check(lib.strait_intf_create(C.cast(init, _vp) if init is not None else None, C.byref(self.handle)))
+
+    def params(self) -> np.ndarray:
+        p = IntfParams()
+        _check(lib.strait_intf_get_params(self.handle, C.cast(C.byref(p), _vp)))
+        return p.as_vector()
+
+    def predict(self, m_avg, self_cmp, self_mem, prio, t_isol=0.0):
+        m, intf, tk = _f64v(m_avg), _f64(), _f64()
+        _check(lib.strait_intf_predict(self.handle, _np_ptr(m), self_cmp, self_mem, prio, t_isol, C.byref(intf), C.byref(tk)))
+        return intf.value, tk.value
+
+    def update(self, m_avg, self_cmp, self_mem, prio, intf_actual) -> float:
+        m, loss = _f64v(m_avg), _f64()
+        _check(lib.strait_intf_update(self.handle, _np_ptr(m), self_cmp, self_mem, prio, intf_actual, C.byref(loss)))
+        return loss.value
+
+    def arrive(self, t_ns, m) -> int:
+        mm, bid = _f64v(m), C.c_uint64()
+        _check(lib.strait_intf_arrive(self.handle, t_ns, _np_ptr(mm), C.byref(bid)))
+        return bid.value
+
+    def depart(self, batch_id, t_ns) -> np.ndarray:
+        out = np.zeros(INTF_METRICS)
+        _check(lib.strait_intf_depart(self.handle, batch_id, t_ns, _np_ptr(out)))
+        return out
+
+    def pressure(self, exclude_id=0) -> np.ndarray:
+        out = np.zeros(INTF_METRICS)
+        _check(lib.strait_intf_pressure(self.handle, exclude_id, _np_ptr(out)))
+        return out
+
+    def close(self):
+        if self.handle:
+            _check(lib.strait_intf_destroy(self.handle))
             self.handle = _vp()
