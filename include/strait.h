@@ -122,6 +122,13 @@ strait_status strait_ctx_destroy(strait_ctx* ctx);      /* E_BUSY while models a
  * off leaves the two levels distinguished by their streams only: the A/B for the paper's
  * ablation "without stream priority" (Appendix A.3). */
 strait_status strait_ctx_set_wave_priority(strait_ctx* ctx, int32_t enabled);
+/* Whether strait_submit and strait_run replay the kernel sequence of a batch from a captured
+ * HIP graph (default off).  The paper's runtime executes a compiled graph "from the first kernel to
+ * the last without interruption" (Section 2); here one graph per (instance, batch size, wave
+ * priority) is captured on the second use of that key (kernel launches only: copies and events
+ * stay outside) and replayed with one launch call afterwards.  Results are those of the
+ * kernel-by-kernel path, bit for bit. */
+strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
 
 strait_status strait_model_load(strait_ctx* ctx, const strait_model_desc* desc, strait_model** out);
 strait_status strait_model_free(strait_model* m);       /* E_BUSY with batches in flight    */

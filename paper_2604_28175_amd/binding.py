@@ -67,6 +67,7 @@ _SIGS = {
     "strait_ctx_create": (_i32, [C.POINTER(CtxDesc), C.POINTER(_vp)]),
     "strait_ctx_destroy": (_i32, [_vp]),
     "strait_ctx_set_wave_priority": (_i32, [_vp, _i32]),
+    "strait_ctx_set_graphs": (_i32, [_vp, _i32]),
     "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
     "strait_model_free": (_i32, [_vp]),
     "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
@@ -154,6 +155,9 @@ class Context:
 
     def load(self, weights: bytes, max_batch: int, n_instances: int = 1) -> "Model":
         return Model(self, weights, max_batch, n_instances)
+
+    def set_graphs(self, enabled: bool):
+        _check(lib.strait_ctx_set_graphs(self.handle, 1 if enabled else 0))
 
     def set_wave_priority(self, enabled: bool):
         _check(lib.strait_ctx_set_wave_priority(self.handle, int(enabled)))

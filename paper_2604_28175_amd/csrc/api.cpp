@@ -120,7 +120,42 @@ strait_status strait_ctx_set_wave_priority(strait_ctx* c, int32_t enabled) {
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_graphs(strait_ctx* c, int32_t enabled) {
+    if (!c) { set_error("ctx_set_graphs: null"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->use_graphs = enabled != 0;
+    return STRAIT_OK;
+}
+
 static int hp_flag(const Context* c, int prio) { return prio == STRAIT_PRIO_HIGH && c->wave_priority; }
+
+// The kernel sequence of one batch on `s`: launched kernel by kernel, or, when the context asks for
+// graphs, as one replay of the sequence captured for this (instance, batch, wave-priority) key.
+// Only kernel launches are captured (no copies, events or memsets).
+static int run_batch(Model& m, Instance& in, int batch, hipStream_t s, int hp) {
+    if (!m.ctx->use_graphs) return run_plan(m, in, batch, s, hp, -1, false);
+    const std::pair<int, int> key(batch, hp);
+    auto it = in.graphs.find(key);
+    if (it == in.graphs.end()) {
+        if (in.warmed.insert(key).second) return run_plan(m, in, batch, s, hp, -1, false);
+        hipGraph_t g = nullptr;
+        HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+        const int rc = run_plan(m, in, batch, s, hp, -1, false);
+        const hipError_t e = hipStreamEndCapture(s, &g);
+        if (rc || e != hipSuccess) {
+            if (g) (void)hipGraphDestroy(g);
+            if (!rc) set_error("graph capture failed: %s", hipGetErrorString(e));
+            return rc ? rc : STRAIT_E_HIP;
+        }
+        hipGraphExec_t ex = nullptr;
+        const hipError_t ei = hipGraphInstantiate(&ex, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (ei != hipSuccess) { set_error("graph instantiate failed: %s", hipGetErrorString(ei)); return STRAIT_E_HIP; }
+        it = in.graphs.emplace(key, ex).first;
+    }
+    HIP_TRY(hipGraphLaunch(it->second, s));
+    return 0;
+}
 
 static void free_instance(Instance& in) {
     if (in.pinned_in) (void)hipHostFree(in.pinned_in);
@@ -133,6 +168,7 @@ static void free_instance(Instance& in) {
     hipEvent_t evs[5] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : in.layer_ev) if (e) (void)hipEventDestroy(e);
+    for (auto& kv : in.graphs) (void)hipGraphExecDestroy(kv.second);
     in = Instance();
 }
 
@@ -300,7 +336,7 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
     rc = hipSetDevice(c->device) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = enqueue_h2d(m, in, batch, host_in, valid_len, cs, s);
     if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = run_plan(*m, in, batch, s, hp_flag(c, prio), -1, false);
+    if (!rc) rc = run_batch(*m, in, batch, s, hp_flag(c, prio));
     if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
     if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
@@ -367,7 +403,7 @@ strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio
     int rc = check_call(m, instance, prio, batch);
     if (rc) return rc;
     HIP_TRY(hipSetDevice(m->ctx->device));
-    return run_plan(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), hp_flag(m->ctx, prio), -1, false);
+    return run_batch(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), hp_flag(m->ctx, prio));
 }
 
 strait_status strait_copy_out(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, void* host_out) {

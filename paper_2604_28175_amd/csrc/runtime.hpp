@@ -8,6 +8,7 @@
 #include <deque>
 #include <map>
 #include <mutex>
+#include <set>
 #include <string>
 #include <thread>
 #include <vector>
@@ -62,6 +63,10 @@ struct Instance {
     std::vector<void*> bufs;
     hipEvent_t ev_h2d0 = nullptr, ev_h2d1 = nullptr, ev_k0 = nullptr, ev_k1 = nullptr, ev_done = nullptr;
     std::vector<hipEvent_t> layer_ev;
+    // Captured kernel sequences, keyed by (batch, wave-priority flag); a key is captured on its second
+    // use, after one eager pass has set the kernels' attributes outside of any capture.
+    std::map<std::pair<int, int>, hipGraphExec_t> graphs;
+    std::set<std::pair<int, int>> warmed;
     bool busy = false;
 };
 
@@ -113,6 +118,7 @@ struct Context {
     std::condition_variable cv_work, cv_done;
     bool stop = false;
     bool wave_priority = true;
+    bool use_graphs = false;
     unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;
     int n_models = 0, next_model_id = 0;
 };

@@ -136,3 +136,33 @@ def test_submit_errors_and_pool(ctx):
     with pytest.raises(S.StraitError) as e:
         ctx.load(b"STRX" + bytes(100), 1, 1)
     assert e.value.status == S.E_FORMAT
+
+
+@pytest.mark.parametrize("arch,batch", [("resnet50", 3), ("mobilenet_v2", 4), ("encoder", 2)])
+def test_graph_replay_equals_kernel_by_kernel(ctx, arch, batch):
+    """The captured-graph path replays the very same launches: every replay, on fresh inputs and with
+    kernel-by-kernel passes and synchronisations in between, must equal the eager result bit for bit."""
+    S = ctx.S
+    if arch == "encoder":
+        md = synth.encoder(5, layers=2, hidden=128, heads=2, ffn=256, seq=64)
+    else:
+        md = getattr(synth, arch)(5, hw=64)
+    m = ctx.load(synth.pack(md), max_batch=batch, n_instances=2)
+    try:
+        for rep in range(5):                      # first use of a key runs eagerly, the second captures, later ones replay
+            if arch == "encoder":
+                x, vl = synth.token_batch(md, batch, 50 + rep)
+            else:
+                x, vl = synth.default_image_batch(md, batch, 50 + rep), None
+            for prio in (S.PRIO_HIGH, S.PRIO_LOW):
+                ctx.set_graphs(False)
+                eager = m.new_output(batch)
+                m.wait(m.submit(prio, x, vl, eager))
+                ctx.set_graphs(True)
+                replay = m.new_output(batch)
+                rec = m.wait(m.submit(prio, x, vl, replay))
+                assert np.array_equal(eager.view(np.uint8), replay.view(np.uint8)), (arch, rep, prio)
+                assert rec.kernel_ms > 0
+    finally:
+        ctx.set_graphs(False)
+        m.free()
