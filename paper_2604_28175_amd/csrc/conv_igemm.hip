@@ -318,7 +318,7 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST>
 __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const ConvParams p) {
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
@@ -517,47 +517,85 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
 
     // ---- epilogue (same as the first kernel's staged path) --------------------------------------
     // ReLU / ReLU6 / none are one clamp with workgroup-uniform bounds; GELU is a separate instantiation
+    // The epilogue's arithmetic after the bias is done on packed fp16 pairs: adding two fp16 numbers, or
+    // clamping one against 0, 6 or an infinity, gives the same fp16 result whether it is done in fp16 or
+    // in fp32 and then rounded, and it takes a quarter of the instructions (short-reduction layers spend
+    // most of their instructions here).  Bias and residual are fetched where they are used: holding
+    // them across the staging costs enough registers to lose a wave per SIMD.  The exception (HOIST) are
+    // the small tiles of the streaming layers that add a residual: there the values are few, the layer
+    // is all epilogue, and requesting bias and residual before the staging barrier takes their latency
+    // off the path between the last MFMA and the stores.
+    constexpr int CPR = BN / 8, NCH = BM * CPR / NT;
     half_t* Cs = smem;
     const bool fuse_act = (p.res == nullptr);
-    const float lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? 0.f : -INFINITY;
-    const float hi = p.act == ACT_RELU6 ? 6.f : INFINITY;
-    auto activate = [&](float v) {
-        if (GELU) v = gelu_f(v);
-        return fminf(fmaxf(v, lo), hi);
+    const half_t lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? (half_t)0.f : (half_t)-INFINITY;
+    const half_t hi = p.act == ACT_RELU6 ? (half_t)6.f : (half_t)INFINITY;
+    const half_t lo1 = fuse_act ? lo : (half_t)-INFINITY, hi1 = fuse_act ? hi : (half_t)INFINITY;
+    const half4 lo4 = {lo1, lo1, lo1, lo1}, hi4 = {hi1, hi1, hi1, hi1};
+    const half8 lo8 = {lo, lo, lo, lo, lo, lo, lo, lo}, hi8 = {hi, hi, hi, hi, hi, hi, hi, hi};
+    auto residual_chunk = [&](int i) {
+        const int id = tid + i * NT;
+        const int row = id / CPR, c8 = id - row * CPR;
+        const int m = m0 + row, n = n0 + c8 * 8;
+        half8 r;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = (half_t)0.f;
+        if (m < p.M && n < p.Cout) r = *(const half8*)(p.res + (long long)m * p.ldy + n);
+        return r;
     };
+    auto bias4 = [&](int a, int g, float (&bv)[4]) {
+        const int cn = n0 + wn0 + a * 32 + 8 * g + 4 * lh;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bv[j] = (p.bias && (cn + j) < p.Cout) ? p.bias[cn + j] : 0.f;
+    };
+    half8 rv[HOIST ? NCH : 1];
+    float bvh[HOIST ? TNB : 1][4][4];
+    if (HOIST) {
+#pragma unroll
+        for (int a = 0; a < TNB; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) bias4(a, g, bvh[a][g]);
+        if (!fuse_act) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) rv[i] = residual_chunk(i);
+        }
+    }
 #pragma unroll
     for (int a = 0; a < TNB; ++a)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int cn = wn0 + a * 32 + 8 * g + 4 * lh;
             float bv[4];
+            if (HOIST) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = (p.bias && (n0 + cn + j) < p.Cout) ? p.bias[n0 + cn + j] : 0.f;
+                for (int j = 0; j < 4; ++j) bv[j] = bvh[a][g][j];
+            } else {
+                bias4(a, g, bv);
+            }
 #pragma unroll
             for (int b = 0; b < TMB; ++b) {
                 half4 h;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     float v = acc[a][b][4 * g + j] + bv[j];
-                    if (fuse_act) v = activate(v);
+                    if (GELU) v = gelu_f(v);
                     h[j] = (half_t)v;
                 }
+                h = __builtin_elementwise_min(__builtin_elementwise_max(h, lo4), hi4);
                 *(half4*)(Cs + (wm0 + b * 32 + l32) * LDC + cn) = h;
             }
         }
     __syncthreads();
-    constexpr int CPR = BN / 8;
 #pragma unroll
-    for (int i = 0; i < BM * CPR / NT; ++i) {
+    for (int i = 0; i < NCH; ++i) {
         const int id = tid + i * NT;
         const int row = id / CPR, c8 = id - row * CPR;
         const int m = m0 + row, n = n0 + c8 * 8;
         if (m < p.M && n < p.Cout) {
             half8 v = *(const half8*)(Cs + row * LDC + c8 * 8);
             if (!fuse_act) {
-                const half8 rv = *(const half8*)(p.res + (long long)m * p.ldy + n);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (half_t)activate((float)v[j] + (float)rv[j]);
+                const half8 r = HOIST ? rv[i] : residual_chunk(i);
+                v = __builtin_elementwise_min(__builtin_elementwise_max(v + r, lo8), hi8);
             }
             *(half8*)((half_t*)p.y + (long long)m * p.ldy + n) = v;
         }
@@ -618,9 +656,11 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
         return 0;
     };
     int rc;
-    if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, true>);
-    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false>);
-    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false>);
+    constexpr bool small_tile = BM * BN <= 128 * 64;
+    if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, true, false>);
+    else if (mode == MODE_1X1 && small_tile && p.res && p.ksplit == 1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, small_tile>);
+    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, false>);
+    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false, false>);
     if (rc) return rc;
     if (p.ksplit > 1) {
         const long long n8 = (long long)p.M * (p.Cout / 8);
@@ -630,6 +670,7 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
     return 0;
 }
+
 
 template <int BM, int BN>
 static int launch_tile(const ConvParams& p, int mode, bool staged, hipStream_t stream) {
@@ -670,7 +711,8 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
     const long long lead = (long long)p.pad_h * p.sH + (long long)p.pad_w * p.sW;
     const bool small = (p.x_elems + lead) * 2 <= 0x7fffffffLL && (long long)p.Cout * p.ldw * 2 <= 0x7fffffffLL;
     p.ksplit = 1;
-    const bool regular = mode == MODE_1X1 || (mode == MODE_GATHER8 && p.C % 32 == 0 && p.R * p.S <= 32 && p.act != ACT_GELU);
+    // (GELU after a residual add is left to the first kernel: this one applies GELU before the staging)
+    const bool regular = (mode == MODE_1X1 && !(p.act == ACT_GELU && p.res)) || (mode == MODE_GATHER8 && p.C % 32 == 0 && p.R * p.S <= 32 && p.act != ACT_GELU);
     // Few output tiles and a long reduction (small batches, late layers): one workgroup per tile
     // would leave most CUs idle behind a serial chain of slices.  Split the reduction over
     // ksplit workgroups per tile, each writing an fp32 slab, and reduce in a second launch.

@@ -47,6 +47,7 @@ CONV_CASES = [
     (4, 1, 1, 64, 10, 1, 1, 0, 0, False, True),         # FC as 1x1 conv, fp32 logits
     (1, 40, 40, 64, 64, 3, 1, 1, 1, False, False),      # several 128-pixel tiles and a ragged tail (M = 1600)
     (1, 7, 7, 512, 512, 3, 1, 1, 1, False, False),      # long reduction (K = 4608), small M
+    (11, 56, 56, 64, 256, 1, 1, 0, 1, True, False),     # 64 -> 256 pointwise with residual, M = 34496: many tiles, ragged tail, residual requested early
 ]
 
 
@@ -223,3 +224,4 @@ def test_gemm_gelu_and_ragged_k(S):
         ref = act_ref(ops.linear(x, w, b), act)
         y = S.k_gemm(dev(S, x), dev(S, w), dev(S, b), act)
         check_kernel(y.float().cpu().numpy(), ref, f"gemm {M}x{N}x{K} act {act}")
+
