@@ -319,7 +319,7 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST>
-__global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const ConvParams p) {
+__global__ void __launch_bounds__(64 * WGM * WGN, (HOIST && BM * BN == 128 * 64) ? 5 : 1) conv_igemm_dma_kernel(const ConvParams p) {
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
     constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
@@ -351,11 +351,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
         logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
     }
     // split-K: the grid holds ksplit copies of the tile grid; copy z reduces slices [k_begin, k_end)
-    const int ntiles = gridDim.x / p.ksplit;
-    const int zsplit = logical / ntiles;
-    const int tile = logical - zsplit * ntiles;
-    const int m0 = (tile / tiles_n) * BM;
-    const int n0 = (tile % tiles_n) * BN;
+    int zsplit = 0, tile = logical;
+    if (p.ksplit > 1) {
+        const int ntiles = gridDim.x / p.ksplit;
+        zsplit = logical / ntiles;
+        tile = logical - zsplit * ntiles;
+    }
+    int tm;                                             // tiles_n is a power of two for every served layer
+    if (p.tiles_n_shift >= 0) tm = tile >> p.tiles_n_shift; else tm = tile / tiles_n;
+    const int m0 = tm * BM;
+    const int n0 = (tile - tm * tiles_n) * BN;
 
     // The input buffer starts `lead` elements before x so that the per-lane offset of an output
     // pixel (its window's top-left tap, which may lie in the padding) is never negative.
@@ -455,6 +460,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
+    // The tile's bias row goes to LDS with the very first transfer (channels past Cout, or no bias at all,
+    // arrive as zeros), so that the epilogue does not start with a round trip to L2.
+    constexpr unsigned BIAS_LDS = (STAGES * STAGE > BM * LDC ? STAGES * STAGE : BM * LDC) * 2;   // byte offset
+    static_assert(BN <= 256, "bias row: one transfer carries 256 floats");
+    if (wave == 0) {
+        const intx4 brsrc = make_rsrc(p.bias, p.bias ? (unsigned)p.Cout * 4u : 0u);
+        const int c = n0 + lane * 4;
+        dma16(brsrc, (p.bias && lane * 4 < BN && c + 3 < p.Cout) ? (unsigned)c * 4u : OOB_OFFSET, 0u, lds0 + BIAS_LDS);
+    }
+
 #pragma unroll
     for (int i = 0; i < STAGES - 1; ++i) issue(i);
 
@@ -523,8 +538,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
     // most of their instructions here).  Bias and residual are fetched where they are used: holding
     // them across the staging costs enough registers to lose a wave per SIMD.  The exception (HOIST) are
     // the small tiles of the streaming layers that add a residual: there the values are few, the layer
-    // is all epilogue, and requesting bias and residual before the staging barrier takes their latency
-    // off the path between the last MFMA and the stores.
+    // is all epilogue, and requesting the residual before the staging barrier takes its latency off the
+    // path between the last MFMA and the stores.
     constexpr int CPR = BN / 8, NCH = BM * CPR / NT;
     half_t* Cs = smem;
     const bool fuse_act = (p.res == nullptr);
@@ -543,22 +558,15 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
         if (m < p.M && n < p.Cout) r = *(const half8*)(p.res + (long long)m * p.ldy + n);
         return r;
     };
+    const float* bias_s = (const float*)((const char*)smem + BIAS_LDS);
     auto bias4 = [&](int a, int g, float (&bv)[4]) {
-        const int cn = n0 + wn0 + a * 32 + 8 * g + 4 * lh;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bv[j] = (p.bias && (cn + j) < p.Cout) ? p.bias[cn + j] : 0.f;
+        const float4 b4 = *(const float4*)(bias_s + wn0 + a * 32 + 8 * g + 4 * lh);
+        bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
     };
     half8 rv[HOIST ? NCH : 1];
-    float bvh[HOIST ? TNB : 1][4][4];
-    if (HOIST) {
+    if (HOIST && !fuse_act) {
 #pragma unroll
-        for (int a = 0; a < TNB; ++a)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) bias4(a, g, bvh[a][g]);
-        if (!fuse_act) {
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) rv[i] = residual_chunk(i);
-        }
+        for (int i = 0; i < NCH; ++i) rv[i] = residual_chunk(i);
     }
 #pragma unroll
     for (int a = 0; a < TNB; ++a)
@@ -566,12 +574,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_igemm_dma_kernel(const Co
         for (int g = 0; g < 4; ++g) {
             const int cn = wn0 + a * 32 + 8 * g + 4 * lh;
             float bv[4];
-            if (HOIST) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) bv[j] = bvh[a][g][j];
-            } else {
-                bias4(a, g, bv);
-            }
+            bias4(a, g, bv);
 #pragma unroll
             for (int b = 0; b < TMB; ++b) {
                 half4 h;
@@ -643,8 +646,14 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN) * p.ksplit;
     if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
     constexpr unsigned ring = STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
-    constexpr unsigned lds = ring > ctile ? ring : ctile;    // the epilogue parks the output tile in the same LDS
+    constexpr unsigned lds = (ring > ctile ? ring : ctile) + 1024;    // the epilogue parks the output tile in the ring's LDS; + the tile's bias row
     dim3 grid((unsigned)tiles), block(64 * WGM * WGN);
+    ConvParams q = p;
+    {
+        const int tn = (p.Cout + BN - 1) / BN;
+        q.tiles_n_shift = -1;
+        for (int sft = 0; sft < 31; ++sft) if ((1 << sft) == tn) q.tiles_n_shift = sft;
+    }
     auto go = [&](auto kernel) -> int {
         static bool configured = false;                 // one flag per instantiation
         if (!configured && lds > 48 * 1024) {
@@ -652,7 +661,7 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
             if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
         }
         configured = true;
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, p);
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, q);
         return 0;
     };
     int rc;
@@ -664,7 +673,7 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     if (rc) return rc;
     if (p.ksplit > 1) {
         const long long n8 = (long long)p.M * (p.Cout / 8);
-        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream, q);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }

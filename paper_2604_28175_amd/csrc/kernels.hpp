@@ -40,6 +40,7 @@ struct ConvParams {
     float* ws;               // optional split-K workspace (16-byte aligned) and its size in bytes
     size_t ws_bytes;
     int ksplit;              // filled in by launch_conv
+    int tiles_n_shift;       // log2 of the number of tiles along Cout, or -1; filled in by the launcher
 };
 
 int launch_conv(const ConvParams& p, hipStream_t stream);
