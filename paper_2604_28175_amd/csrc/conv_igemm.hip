@@ -318,8 +318,19 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// Waves per SIMD that the LDS footprint of a tile configuration allows (the register allocator is asked
+// for that many: left to itself it splits accumulators into AGPRs and loses waves for nothing).
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+constexpr int dma_tile_waves_per_simd() {
+    constexpr int ring = STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
+    constexpr int lds = (ring > ctile ? ring : ctile) + 1024;
+    constexpr int blocks = 160 * 1024 / lds;
+    constexpr int w = blocks * WGM * WGN / 4;
+    return w < 1 ? 1 : (w > 8 ? 8 : w);
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST>
-__global__ void __launch_bounds__(64 * WGM * WGN, (HOIST && BM * BN == 128 * 64) ? 5 : 1) conv_igemm_dma_kernel(const ConvParams p) {
+__global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, BN, BK, WGM, WGN, STAGES>())) conv_igemm_dma_kernel(const ConvParams p) {
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
     constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
@@ -536,10 +547,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (HOIST && BM * BN == 128 * 64)
     // clamping one against 0, 6 or an infinity, gives the same fp16 result whether it is done in fp16 or
     // in fp32 and then rounded, and it takes a quarter of the instructions (short-reduction layers spend
     // most of their instructions here).  Bias and residual are fetched where they are used: holding
-    // them across the staging costs enough registers to lose a wave per SIMD.  The exception (HOIST) are
-    // the small tiles of the streaming layers that add a residual: there the values are few, the layer
-    // is all epilogue, and requesting the residual before the staging barrier takes its latency off the
-    // path between the last MFMA and the stores.
+    // them across the reduction would cost a wave per SIMD in registers.  Layers that add a residual
+    // (HOIST) request it right after the reduction, before the staging barrier: that takes its latency
+    // off the path between the last MFMA and the stores.
     constexpr int CPR = BN / 8, NCH = BM * CPR / NT;
     half_t* Cs = smem;
     const bool fuse_act = (p.res == nullptr);
@@ -665,9 +675,8 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
         return 0;
     };
     int rc;
-    constexpr bool small_tile = BM * BN <= 128 * 64;
     if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, true, false>);
-    else if (mode == MODE_1X1 && small_tile && p.res && p.ksplit == 1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, small_tile>);
+    else if (mode == MODE_1X1 && p.res && p.ksplit == 1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, true>);
     else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, false>);
     else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false, false>);
     if (rc) return rc;
