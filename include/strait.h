@@ -284,6 +284,63 @@ strait_status strait_intf_depart(strait_intf* p, uint64_t batch_id, int64_t t_ns
 /* Summed demand of the batches running now, leaving out exclude_id (0 = none). */
 strait_status strait_intf_pressure(const strait_intf* p, uint64_t exclude_id, double* m_now);
 
+/* ---- scheduling policy (host only; no GPU needed) ---------------------------------------------
+ * Section 3.3 of the paper, Algorithm 1, on top of Eq. 1:
+ *     T_inf(B_ik) = T_inf_isol(B_ik) + T_data + T_kernel(B_ik) + T_queue
+ * A strait_sched owns, per GPU, a link model (Eq. 2-3) and a co-location tracker, and one interference
+ * predictor (Eq. 4-6).  strait_sched_decide serves one model's queue once: requests that could not
+ * finish even in isolation are dropped; a binary search finds the largest batch size k that some GPU
+ * can take with not violate() and meet(); among those GPUs the one of lowest estimated T_inf gets the
+ * batch, which is logged as running there.  violate(): a low-priority batch may not lift the summed peak
+ * throughput (largest demand metric) of the low-priority batches on the GPU above C_low, and no running
+ * batch of equal or higher priority may be pushed past its deadline (completed fraction from the elapsed
+ * kernel time under its time-weighted pressure so far, the rest under the pressure with the new batch
+ * added).  meet(): the new batch meets its own deadline with T_kernel taken at half of the GPU's summed
+ * demand.  C_low rises by 0.25 % per full 100 ms from 75 % to 100 % and returns to 75 % when a
+ * high-priority batch misses its deadline.  Times are int64 nanoseconds on one clock, never decreasing
+ * across calls.  Thread-safe. */
+typedef struct strait_batch_profile {          /* offline profile of one (model, batch size)           */
+    double t_inf_isol_ns;                      /* p95 isolated overall latency                         */
+    int64_t t_htod_ns;                         /* p95 isolated host-to-device transfer time            */
+    double t_kernel_isol_ns;                   /* p95 isolated kernel latency                          */
+    double m[STRAIT_INTF_METRICS];             /* resource demand (strait_intf_demand)                 */
+    double m_self_cmp, m_self_mem;
+} strait_batch_profile;
+typedef struct strait_decision {
+    int32_t n_dropped;                         /* requests removed from the front of the queue         */
+    int32_t batch;                             /* size of the batch to submit (the next `batch` requests), 0 = deferred */
+    int32_t gpu;                               /* where; -1 when deferred                               */
+    int32_t reserved;
+    double t_inf_ns;                           /* Eq. 1 for the chosen batch and GPU                   */
+    int64_t t_data_ns;                         /* its Eq. 2 term                                        */
+    uint64_t running_id;                       /* handle for strait_sched_complete                     */
+} strait_decision;
+typedef struct strait_completion {
+    int32_t violated;                          /* finished after its deadline                           */
+    int32_t reserved;
+    double loss;                               /* Huber loss of the predictor before its update        */
+    double m_avg[STRAIT_INTF_METRICS];         /* time-weighted co-located demand it ran under         */
+    double c_low;
+} strait_completion;
+typedef struct strait_sched strait_sched;
+/* init == NULL: the conservative predictor start of strait_intf_create. */
+strait_status strait_sched_create(int32_t n_gpus, const strait_intf_params* init, strait_sched** out);
+strait_status strait_sched_destroy(strait_sched* s);
+/* table[b-1] is the profile of batch size b, b = 1..max_batch; E_BUSY while batches of the model run. */
+strait_status strait_sched_set_profile(strait_sched* s, int32_t model_id, int32_t priority,
+                                       const strait_batch_profile* table, int32_t max_batch);
+/* Advance the AIMD clock; c_low (optional) receives the cap. */
+strait_status strait_sched_tick(strait_sched* s, int64_t now_ns, double* c_low);
+/* enqueue_ns / deadline_ns: the buffered requests of the model, oldest first. */
+strait_status strait_sched_decide(strait_sched* s, int32_t model_id, int64_t now_ns, const int64_t* enqueue_ns,
+                                  const int64_t* deadline_ns, int32_t n_requests, strait_decision* out);
+/* The batch finished at now_ns with measured kernel latency kernel_ns; h2d_end_ns >= 0 calibrates the
+ * link with the measured end of its transfer.  Removes it from the running list, updates the predictor
+ * (Section 3.2, "Self-adaptive model") and the cap.  out may be NULL. */
+strait_status strait_sched_complete(strait_sched* s, int32_t gpu, uint64_t running_id, int64_t now_ns,
+                                    double kernel_ns, int64_t h2d_end_ns, strait_completion* out);
+strait_status strait_sched_get_params(strait_sched* s, strait_intf_params* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -106,6 +106,13 @@ _SIGS = {
     "strait_intf_arrive": (_i32, [_vp, _i64, _vp, C.POINTER(C.c_uint64)]),
     "strait_intf_depart": (_i32, [_vp, C.c_uint64, _i64, _vp]),
     "strait_intf_pressure": (_i32, [_vp, C.c_uint64, _vp]),
+    "strait_sched_create": (_i32, [_i32, _vp, C.POINTER(_vp)]),
+    "strait_sched_destroy": (_i32, [_vp]),
+    "strait_sched_set_profile": (_i32, [_vp, _i32, _i32, _vp, _i32]),
+    "strait_sched_tick": (_i32, [_vp, _i64, C.POINTER(_f64)]),
+    "strait_sched_decide": (_i32, [_vp, _i32, _i64, _vp, _vp, _i32, _vp]),
+    "strait_sched_complete": (_i32, [_vp, _i32, C.c_uint64, _i64, _f64, _i64, _vp]),
+    "strait_sched_get_params": (_i32, [_vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -437,8 +444,8 @@ class Interference:
 
     def __init__(self, params=None):
         self.handle = _vp()
-        init = None if params is None else C.byref(IntfParams.from_vector(params))
-        _check(lib.strait_intf_create(C.cast(init, _vp) if init is not None else None, C.byref(self.handle)))
+        start = None if params is None else IntfParams.from_vector(params)      # must outlive the call
+        _check(lib.strait_intf_create(None if start is None else C.cast(C.byref(start), _vp), C.byref(self.handle)))
 
     def params(self) -> np.ndarray:
         p = IntfParams()
@@ -473,4 +480,66 @@ class Interference:
     def close(self):
         if self.handle:
             _check(lib.strait_intf_destroy(self.handle))
+            self.handle = _vp()
+
+
+class BatchProfile(C.Structure):
+    """strait_batch_profile."""
+    _fields_ = [("t_inf_isol_ns", _f64), ("t_htod_ns", _i64), ("t_kernel_isol_ns", _f64), ("m", _f64 * INTF_METRICS),
+                ("m_self_cmp", _f64), ("m_self_mem", _f64)]
+
+
+class Decision(C.Structure):
+    """strait_decision."""
+    _fields_ = [("n_dropped", _i32), ("batch", _i32), ("gpu", _i32), ("reserved", _i32), ("t_inf_ns", _f64),
+                ("t_data_ns", _i64), ("running_id", C.c_uint64)]
+
+
+class Completion(C.Structure):
+    """strait_completion."""
+    _fields_ = [("violated", _i32), ("reserved", _i32), ("loss", _f64), ("m_avg", _f64 * INTF_METRICS), ("c_low", _f64)]
+
+
+class Scheduler:
+    """strait_sched: the scheduling policy over the link and interference models (host only)."""
+
+    def __init__(self, n_gpus: int = 1, params=None):
+        self.handle = _vp()
+        start = None if params is None else IntfParams.from_vector(params)      # must outlive the call
+        _check(lib.strait_sched_create(n_gpus, None if start is None else C.cast(C.byref(start), _vp), C.byref(self.handle)))
+
+    def set_profile(self, model_id: int, priority: int, profiles):
+        """profiles: one (t_inf_isol_ns, t_htod_ns, t_kernel_isol_ns, m[5], m_self_cmp, m_self_mem) per batch size 1.."""
+        arr = (BatchProfile * len(profiles))()
+        for i, (ti, th, tk, m, sc, sm) in enumerate(profiles):
+            arr[i] = BatchProfile(float(ti), int(th), float(tk), (_f64 * INTF_METRICS)(*[float(v) for v in m]), float(sc), float(sm))
+        _check(lib.strait_sched_set_profile(self.handle, model_id, priority, C.cast(arr, _vp), len(profiles)))
+
+    def tick(self, now_ns: int) -> float:
+        c = _f64()
+        _check(lib.strait_sched_tick(self.handle, now_ns, C.byref(c)))
+        return c.value
+
+    def decide(self, model_id: int, now_ns: int, enqueue_ns, deadline_ns) -> Decision:
+        e = np.ascontiguousarray(enqueue_ns, dtype=np.int64)
+        d = np.ascontiguousarray(deadline_ns, dtype=np.int64)
+        assert e.size == d.size
+        out = Decision()
+        _check(lib.strait_sched_decide(self.handle, model_id, now_ns, _np_ptr(e) if e.size else None, _np_ptr(d) if d.size else None,
+                                       e.size, C.cast(C.byref(out), _vp)))
+        return out
+
+    def complete(self, gpu: int, running_id: int, now_ns: int, kernel_ns: float, h2d_end_ns: int = -1) -> Completion:
+        out = Completion()
+        _check(lib.strait_sched_complete(self.handle, gpu, running_id, now_ns, kernel_ns, h2d_end_ns, C.cast(C.byref(out), _vp)))
+        return out
+
+    def params(self) -> np.ndarray:
+        p = IntfParams()
+        _check(lib.strait_sched_get_params(self.handle, C.cast(C.byref(p), _vp)))
+        return p.as_vector()
+
+    def close(self):
+        if self.handle:
+            _check(lib.strait_sched_destroy(self.handle))
             self.handle = _vp()
