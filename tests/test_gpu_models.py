@@ -166,3 +166,24 @@ def test_graph_replay_equals_kernel_by_kernel(ctx, arch, batch):
     finally:
         ctx.set_graphs(False)
         m.free()
+
+
+def test_small_batch_split_reduction_is_reproducible(ctx):
+    """Small batches split long reductions over several workgroups per tile; the partial results are summed
+    in a fixed order, so repeated runs must agree bit for bit, at either priority."""
+    S = ctx.S
+    md = synth.resnet50(9, hw=64)
+    x = synth.default_image_batch(md, 2, 3)
+    m = ctx.load(synth.pack(md), max_batch=2, n_instances=2)
+    try:
+        outs = []
+        for rep in range(6):
+            out = m.new_output(2)
+            m.wait(m.submit(S.PRIO_HIGH if rep % 2 else S.PRIO_LOW, x, None, out))
+            outs.append(out.copy())
+        for o in outs[1:]:
+            assert np.array_equal(o.view(np.uint8), outs[0].view(np.uint8))
+        ref = omodels.resnet50_forward(md.tensors, x)
+        check_logits(m.decode(outs[0], 2)["logits"], ref.logits, m.decode(outs[0], 2)["top1"], "ResNet-50 64px b2 (split reductions)")
+    finally:
+        m.free()
