@@ -89,7 +89,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-batch", action="store_true")
-    ap.add_argument("--colocation-seconds", type=float, default=2.0,
+    ap.add_argument("--colocation-seconds", type=float, default=5.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
     ap.add_argument("--copy-calibration-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for hardware byte counters)")

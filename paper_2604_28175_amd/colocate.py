@@ -10,6 +10,7 @@ request itself (staging, copies, kernels, timing) happens inside the library.
 """
 from __future__ import annotations
 
+import gc
 import threading
 import time
 from dataclasses import dataclass, field
@@ -116,6 +117,8 @@ def run(hp_model, hp_inputs, arrivals_ns, lp_model, lp_inputs, mode: str = "both
     hp, lp = (StreamStats() if mode != "lp_solo" else None), (StreamStats() if mode != "hp_solo" else None)
     stop = threading.Event()
     th: Optional[threading.Thread] = None
+    gc_was_on = gc.isenabled()
+    gc.disable()                                  # a collection pause in the submitting thread would show up as request latency
     if lp is not None:
         th = threading.Thread(target=_back_to_back, args=(lp_model, S.PRIO_LOW, lp_inputs, None, stop, lp), daemon=True)
         th.start()
@@ -129,4 +132,6 @@ def run(hp_model, hp_inputs, arrivals_ns, lp_model, lp_inputs, mode: str = "both
         stop.set()
         if th is not None:
             th.join()
+        if gc_was_on:
+            gc.enable()
     return hp, lp
