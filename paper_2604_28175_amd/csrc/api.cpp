@@ -95,6 +95,8 @@ strait_status strait_ctx_create(const strait_ctx_desc* d, strait_ctx** out) {
         w->stream = i < c->hp.size() ? c->hp[i] : c->lp[i - c->hp.size()];
         c->workers.push_back(w);
     }
+    c->compute_mu.resize(c->workers.size());
+    c->copy_mu.resize(c->copy.size());
     for (StreamWorker* w : c->workers) w->th = std::thread(worker_loop, (Context*)c, w);
     *out = c;
     return STRAIT_OK;
@@ -286,20 +288,29 @@ static hipStream_t compute_stream(Context* c, int prio, int instance) {
     return prio == STRAIT_PRIO_HIGH ? c->hp[instance % c->hp.size()] : c->lp[instance % c->lp.size()];
 }
 
-static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* host_in, const int32_t* valid_len,
-                       hipStream_t cs, hipStream_t s) {
+// Index of a compute stream in Context::workers / compute_mu (hp streams first, then lp).
+static size_t compute_index(const Context* c, int prio, unsigned n) {
+    return prio == STRAIT_PRIO_HIGH ? n % c->hp.size() : c->hp.size() + n % c->lp.size();
+}
+
+// Stage the input in the instance's pinned buffer (no lock: this is the slow part and instances are
+// independent), then enqueue event / copy / event on copy stream `ci` as one uninterrupted group.
+static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* host_in, const int32_t* valid_len, size_t ci) {
+    Context* c = m->ctx;
+    hipStream_t cs = c->copy[ci];
     const size_t inb = m->in_bytes(batch);
     memcpy(in.pinned_in, host_in, inb);
-    HIP_TRY(hipEventRecord(in.ev_h2d0, cs));
-    HIP_TRY(hipMemcpyAsync(in.dev_in, in.pinned_in, inb, hipMemcpyHostToDevice, cs));
+    int32_t* pv = nullptr;
     if (m->arch == STRAIT_ARCH_ENCODER) {
         const size_t off = (m->in_bytes(m->max_batch) + 255) / 256 * 256;
-        int32_t* pv = (int32_t*)((char*)in.pinned_in + off);
+        pv = (int32_t*)((char*)in.pinned_in + off);
         for (int i = 0; i < batch; ++i) pv[i] = valid_len[i] < 0 ? 0 : (valid_len[i] > m->seq ? m->seq : valid_len[i]);
-        HIP_TRY(hipMemcpyAsync(in.dev_valid, pv, (size_t)batch * 4, hipMemcpyHostToDevice, cs));
     }
+    std::lock_guard<std::mutex> lk(c->copy_mu[ci]);
+    HIP_TRY(hipEventRecord(in.ev_h2d0, cs));
+    HIP_TRY(hipMemcpyAsync(in.dev_in, in.pinned_in, inb, hipMemcpyHostToDevice, cs));
+    if (pv) HIP_TRY(hipMemcpyAsync(in.dev_valid, pv, (size_t)batch * 4, hipMemcpyHostToDevice, cs));
     HIP_TRY(hipEventRecord(in.ev_h2d1, cs));
-    HIP_TRY(hipStreamWaitEvent(s, in.ev_h2d1, 0));
     return 0;
 }
 
@@ -330,16 +341,29 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
         si = prio == STRAIT_PRIO_HIGH ? c->n_hp_sub++ : c->n_lp_sub++;
         ci = c->n_copy_sub++;
     }
-    const size_t widx = prio == STRAIT_PRIO_HIGH ? si % c->hp.size() : c->hp.size() + si % c->lp.size();
+    const size_t widx = compute_index(c, prio, si);
+    const size_t cidx = ci % c->copy.size();
     hipStream_t s = c->workers[widx]->stream;
-    hipStream_t cs = c->copy[ci % c->copy.size()];
+    hipStream_t cs = c->copy[cidx];
     rc = hipSetDevice(c->device) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = enqueue_h2d(m, in, batch, host_in, valid_len, cs, s);
-    if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = run_batch(*m, in, batch, s, hp_flag(c, prio));
-    if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-    if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+    if (!rc) rc = enqueue_h2d(m, in, batch, host_in, valid_len, cidx);
+    t->model = m; t->instance = idx; t->prio = prio; t->batch = batch; t->host_out = host_out;
+    t->rec.model_id = m->id; t->rec.priority = prio; t->rec.batch = batch; t->rec.instance = idx;
+    t->rec.t_enqueue_ns = t_enq;
+    {
+        std::lock_guard<std::mutex> slk(c->compute_mu[widx]);
+        if (!rc) rc = hipStreamWaitEvent(s, in.ev_h2d1, 0) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) rc = run_batch(*m, in, batch, s, hp_flag(c, prio));
+        if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) {
+            t->rec.t_issued_ns = now_ns();
+            std::lock_guard<std::mutex> lk(c->mu);          // tickets join the worker's queue in stream order
+            c->workers[widx]->q.push_back(t);
+        }
+    }
     if (rc) {
         if (rc == STRAIT_E_HIP && !strait::last_error()[0]) set_error("submit: a HIP call failed");
         (void)hipStreamSynchronize(s);
@@ -347,14 +371,6 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
         release();
         delete t;
         return rc;
-    }
-    t->model = m; t->instance = idx; t->prio = prio; t->batch = batch; t->host_out = host_out;
-    t->rec.model_id = m->id; t->rec.priority = prio; t->rec.batch = batch; t->rec.instance = idx;
-    t->rec.t_enqueue_ns = t_enq;
-    t->rec.t_issued_ns = now_ns();
-    {
-        std::lock_guard<std::mutex> lk(c->mu);
-        c->workers[widx]->q.push_back(t);
     }
     c->cv_work.notify_all();
     *ticket = t;
@@ -396,13 +412,18 @@ strait_status strait_copy_in(strait_model* m, int32_t instance, strait_priority 
     if (m->arch == STRAIT_ARCH_ENCODER && !valid_len) { set_error("copy_in: the encoder needs valid_len"); return STRAIT_E_INVALID; }
     Context* c = m->ctx;
     HIP_TRY(hipSetDevice(c->device));
-    return enqueue_h2d(m, m->inst[instance], batch, host_in, valid_len, c->copy[instance % c->copy.size()], compute_stream(c, prio, instance));
+    rc = enqueue_h2d(m, m->inst[instance], batch, host_in, valid_len, (size_t)instance % c->copy.size());
+    if (rc) return rc;
+    std::lock_guard<std::mutex> slk(c->compute_mu[compute_index(c, prio, (unsigned)instance)]);
+    HIP_TRY(hipStreamWaitEvent(compute_stream(c, prio, instance), m->inst[instance].ev_h2d1, 0));
+    return STRAIT_OK;
 }
 
 strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio, int32_t batch) {
     int rc = check_call(m, instance, prio, batch);
     if (rc) return rc;
     HIP_TRY(hipSetDevice(m->ctx->device));
+    std::lock_guard<std::mutex> slk(m->ctx->compute_mu[compute_index(m->ctx, prio, (unsigned)instance)]);
     return run_batch(*m, m->inst[instance], batch, compute_stream(m->ctx, prio, instance), hp_flag(m->ctx, prio));
 }
 

@@ -114,6 +114,10 @@ struct Context {
     int device = 0;
     std::vector<hipStream_t> hp, lp, copy;
     std::vector<StreamWorker*> workers;     // one per compute stream: hp first, then lp
+    // A batch's operations on a stream (event, copy, event / event, kernels, event, copy, event) are enqueued
+    // under that stream's mutex, so that batches submitted from several threads do not interleave on it and
+    // every record times its own batch only.
+    std::deque<std::mutex> compute_mu, copy_mu;
     std::mutex mu;                          // guards worker queues, ticket completion, counters
     std::condition_variable cv_work, cv_done;
     bool stop = false;

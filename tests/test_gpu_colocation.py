@@ -37,23 +37,62 @@ def test_records_are_consistent(env):
     assert 1e-3 * nbytes / 100e9 * 1e3 < rec.h2d_ms < 2.0
 
 
-def test_concurrent_pinned_copies_serialise(env):
-    """Two 19 MB input copies issued together on two copy streams: the second one's copy ends about
-    one copy time after the first one's (FIFO on the link), it does not share the link's bandwidth
-    for its whole duration."""
+def two_copies(S, ctx, md, batch):
+    """Solo copy time, and the copy times of two batches submitted at the same moment from two threads (each
+    submit first stages its input in pinned memory, which takes longer than the copy itself, so only
+    simultaneous submits make the two copies meet on the link)."""
+    import threading
+    m = ctx.load(synth.pack(md), max_batch=batch, n_instances=2)
+    try:
+        x = synth.default_image_batch(md, batch, 2)
+        outs = [m.new_output(batch), m.new_output(batch)]
+        for _ in range(2):
+            _, solo = m.infer(x, prio=S.PRIO_LOW)
+        best = None
+        for attempt in range(5):                      # keep the attempt in which the copies overlapped most
+            gate, recs = threading.Barrier(2), [None, None]
+
+            def one(i):
+                gate.wait()
+                recs[i] = m.wait(m.submit(S.PRIO_LOW, x, None, outs[i]))
+
+            th = [threading.Thread(target=one, args=(i,)) for i in range(2)]
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+            assert np.array_equal(outs[0], outs[1])
+            pair = (recs[0].h2d_ms, recs[1].h2d_ms)
+            if best is None or sum(pair) > sum(best):
+                best = pair
+        return solo.h2d_ms, best[0], best[1]
+    finally:
+        m.free()
+
+
+def test_copies_on_one_copy_stream_are_first_in_first_out(env):
+    """The transfer model of Section 3.2 (Eq. 2-3) assumes that pinned copies of concurrent batches are served
+    one after the other.  With a single copy stream that is what happens here: each copy, timed on the stream,
+    takes its solo time, however many are queued."""
     S, colocate, ctx, md_hp, hp, md_lp, lp = env
-    x = synth.default_image_batch(md_lp, 64, 2)
-    outs = [lp.new_output(64), lp.new_output(64)]
-    _, solo = lp.infer(x, prio=S.PRIO_LOW)
-    _, solo = lp.infer(x, prio=S.PRIO_LOW)
-    t0 = lp.submit(S.PRIO_LOW, x, None, outs[0])
-    t1 = lp.submit(S.PRIO_LOW, x, None, outs[1])
-    r0, r1 = lp.wait(t0), lp.wait(t1)
-    assert np.array_equal(outs[0], outs[1])
-    # each copy, measured on its own stream, takes between one and about two solo copy times
-    assert r0.h2d_ms < 2.6 * solo.h2d_ms and r1.h2d_ms < 2.6 * solo.h2d_ms
-    assert r0.h2d_ms + r1.h2d_ms > 1.5 * solo.h2d_ms
-    print(f"solo h2d {solo.h2d_ms:.3f} ms; concurrent {r0.h2d_ms:.3f} / {r1.h2d_ms:.3f} ms")
+    one = S.Context(device=0, n_hp=1, n_lp=1, n_copy=1)
+    try:
+        solo, a, b = two_copies(S, one, md_lp, 64)
+        print(f"one copy stream: solo h2d {solo:.3f} ms; two submitted together {a:.3f} / {b:.3f} ms")
+        assert a < 1.35 * solo and b < 1.35 * solo
+    finally:
+        one.close()
+
+
+def test_copies_on_two_copy_streams_share_the_link(env):
+    """On this machine copies on different streams are not serialised by the link: they run at the same time and
+    share its bandwidth, so each takes longer than alone while the pair still needs about two solo times in all.
+    (The first-in first-out model then describes the end of the last copy, not of the first.)"""
+    S, colocate, ctx, md_hp, hp, md_lp, lp = env
+    solo, a, b = two_copies(S, ctx, md_lp, 64)
+    print(f"two copy streams: solo h2d {solo:.3f} ms; two submitted together {a:.3f} / {b:.3f} ms")
+    assert a < 2.6 * solo and b < 2.6 * solo
+    assert a + b > 2.6 * solo          # together they held the link for more than the 2 solo times a queue would give
 
 
 def test_open_loop_colocation_short(env):
