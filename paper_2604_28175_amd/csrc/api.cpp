@@ -167,7 +167,8 @@ static void free_instance(Instance& in) {
     if (in.dev_valid) (void)hipFree(in.dev_valid);
     if (in.splitk_ws) (void)hipFree(in.splitk_ws);
     for (void* b : in.bufs) if (b) (void)hipFree(b);
-    hipEvent_t evs[5] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done};
+    if (in.side) { (void)hipStreamSynchronize(in.side); (void)hipStreamDestroy(in.side); }
+    hipEvent_t evs[7] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done, in.ev_fork, in.ev_join};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : in.layer_ev) if (e) (void)hipEventDestroy(e);
     for (auto& kv : in.graphs) (void)hipGraphExecDestroy(kv.second);
@@ -208,7 +209,10 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
         }
         ok = ok && hipEventCreate(&in.ev_h2d0) == hipSuccess && hipEventCreate(&in.ev_h2d1) == hipSuccess &&
              hipEventCreate(&in.ev_k0) == hipSuccess && hipEventCreate(&in.ev_k1) == hipSuccess &&
-             hipEventCreate(&in.ev_done) == hipSuccess;
+             hipEventCreate(&in.ev_done) == hipSuccess &&
+             hipStreamCreateWithFlags(&in.side, hipStreamNonBlocking) == hipSuccess &&      // default priority
+             hipEventCreateWithFlags(&in.ev_fork, hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&in.ev_join, hipEventDisableTiming) == hipSuccess;
         if (ok) {
             in.layer_ev.resize(m->ops.size() + 1, nullptr);
             for (hipEvent_t& e : in.layer_ev) ok = ok && hipEventCreate(&e) == hipSuccess;

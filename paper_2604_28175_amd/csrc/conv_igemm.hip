@@ -18,6 +18,8 @@
 //     and writes it out (adding the residual, applying the activation) as 16-byte row segments;
 //   - workgroup ids are re-ordered so that tiles sharing an input slice run on the same XCD
 //     (consecutive hardware ids are dealt round-robin over the 8 XCDs, each with its own L2).
+#include <atomic>
+
 #include "kernels.hpp"
 
 namespace strait {
@@ -665,12 +667,12 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
         for (int sft = 0; sft < 31; ++sft) if ((1 << sft) == tn) q.tiles_n_shift = sft;
     }
     auto go = [&](auto kernel) -> int {
-        static bool configured = false;                 // one flag per instantiation
-        if (!configured && lds > 48 * 1024) {
+        static std::atomic<bool> configured{false};     // one flag per instantiation; setting the attribute twice is harmless
+        if (!configured.load(std::memory_order_acquire) && lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
         }
-        configured = true;
+        configured.store(true, std::memory_order_release);
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, q);
         return 0;
     };

@@ -416,19 +416,23 @@ static int plan_resnet50(Model& m, Builder& b) {
             const std::string p(pre);
             const int pln = planes[si], stride = (bi == 0 && si > 0) ? 2 : 1;
             const int P2 = b.osz(P, 3, stride, 1), Q2 = b.osz(Q, 3, stride, 1);
+            // The projection shortcut of a stage's first block depends only on the block input, as does
+            // c1: it is issued first and runs on the side stream beside c1 and c2; c3 joins.
+            int sc = cur;
+            if (bi == 0) {
+                sc = b.pl.get((size_t)P2 * Q2 * pln * 4);
+                if ((rc = b.conv(p + ".down", true, cur, P, Q, cin, pln * 4, 1, stride, 0, ACT_NONE, SLOT_NONE, sc, nullptr, nullptr))) return rc;
+                m.ops.back().side = 1;
+            }
             const int t1 = b.pl.get((size_t)P * Q * pln);
             if ((rc = b.conv(p + ".c1", true, cur, P, Q, cin, pln, 1, 1, 0, ACT_RELU, SLOT_NONE, t1, nullptr, nullptr))) return rc;
             const int t2 = b.pl.get((size_t)P2 * Q2 * pln);
             if ((rc = b.conv(p + ".c2", true, t1, P, Q, pln, pln, 3, stride, 1, ACT_RELU, SLOT_NONE, t2, nullptr, nullptr))) return rc;
             b.pl.put(t1);
-            int sc = cur;
-            if (bi == 0) {
-                sc = b.pl.get((size_t)P2 * Q2 * pln * 4);
-                if ((rc = b.conv(p + ".down", true, cur, P, Q, cin, pln * 4, 1, stride, 0, ACT_NONE, SLOT_NONE, sc, nullptr, nullptr))) return rc;
-                b.pl.put(cur);
-            }
+            if (bi == 0) b.pl.put(cur);
             const int o = b.pl.get((size_t)P2 * Q2 * pln * 4);
             if ((rc = b.conv(p + ".c3", true, t2, P2, Q2, pln, pln * 4, 1, 1, 0, ACT_RELU, sc, o, nullptr, nullptr))) return rc;
+            if (bi == 0) m.ops.back().join = 1;
             b.pl.put(t2);
             b.pl.put(sc);
             cur = o; cin = pln * 4; P = P2; Q = Q2;
@@ -613,8 +617,26 @@ static void* slot_ptr(Model& m, Instance& in, int slot, int ref, int batch) {
 int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed) {
     const int n = (int)m.ops.size();
     if (last_layer < 0 || last_layer >= n) last_layer = n - 1;
+    // Per-layer timing and prefix runs keep everything on the one stream (their events bracket single launches).
+    const bool branches = !timed && last_layer == n - 1 && in.side != nullptr;
+    bool forked = false;
+    hipStream_t main_stream = stream;
     for (int i = 0; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
+        stream = main_stream;
+        // a branch pays a fork and a join (two event hand-overs between streams): only worth it for a launch
+        // of some size; smaller ones stay in line, where they may also split their reduction
+        if (branches && op.side && (long long)batch * op.P * op.Q * op.K >= 8000000LL) {
+            HIP_TRY(hipEventRecord(in.ev_fork, main_stream));
+            HIP_TRY(hipStreamWaitEvent(in.side, in.ev_fork, 0));
+            stream = in.side;
+            forked = true;
+        }
+        if (branches && op.join && forked) {
+            HIP_TRY(hipEventRecord(in.ev_join, in.side));
+            HIP_TRY(hipStreamWaitEvent(main_stream, in.ev_join, 0));
+            forked = false;
+        }
         if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
         const void* src = slot_ptr(m, in, op.in, 0, batch);
         void* dst = slot_ptr(m, in, op.out, op.out_ref, batch);
@@ -631,7 +653,8 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 p.sN = op.sN; p.sH = op.sH; p.sW = op.sW;
                 p.Kg = op.vR * op.vS * op.vC; p.ldw = op.ldw;
                 p.Cout = op.K; p.ldy = op.K; p.act = op.act; p.out_f32 = op.out_f32; p.hp = hp;
-                p.ws = in.splitk_ws; p.ws_bytes = SPLITK_WS_BYTES;
+                // the split-K workspace belongs to the main stream's launches; a branch running beside them goes without
+                if (stream == main_stream) { p.ws = in.splitk_ws; p.ws_bytes = SPLITK_WS_BYTES; }
                 rc = launch_conv(p, stream);
                 break;
             }
@@ -659,9 +682,16 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 set_error("unknown op kind %d", op.kind);
                 rc = STRAIT_E_INVALID;
         }
-        if (rc) return rc;
+        if (rc) {
+            if (forked) { (void)hipEventRecord(in.ev_join, in.side); (void)hipStreamWaitEvent(main_stream, in.ev_join, 0); }
+            return rc;
+        }
     }
-    if (timed) HIP_TRY(hipEventRecord(in.layer_ev[last_layer + 1], stream));
+    if (forked) {                                       // a branch nobody joined: the main stream still waits for it
+        HIP_TRY(hipEventRecord(in.ev_join, in.side));
+        HIP_TRY(hipStreamWaitEvent(main_stream, in.ev_join, 0));
+    }
+    if (timed) HIP_TRY(hipEventRecord(in.layer_ev[last_layer + 1], main_stream));
     return 0;
 }
 

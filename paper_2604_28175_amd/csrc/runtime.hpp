@@ -39,6 +39,9 @@ struct Op {
     int P = 1, Q = 1, K = 1;          // output
     int R = 1, S = 1, stride = 1, pad = 0, act = 0;
     int out_f32 = 0;
+    // Independent branch: `side` ops run on the instance's side stream, forked off the main stream right
+    // before them; the first later op with `join` set waits for the side stream before it is launched.
+    int side = 0, join = 0;
     // implicit-GEMM addressing (elements), see ConvParams
     long long sN = 0; int sH = 0, sW = 0, stride_w = 1, pad_h = 0, pad_w = 0, vC = 0, vR = 0, vS = 0, vH = 0, vW = 0;
     int ldw = 0;
@@ -62,6 +65,8 @@ struct Instance {
     float* splitk_ws = nullptr;        // fp32 slabs of split-K convolutions (small batches)
     std::vector<void*> bufs;
     hipEvent_t ev_h2d0 = nullptr, ev_h2d1 = nullptr, ev_k0 = nullptr, ev_k1 = nullptr, ev_done = nullptr;
+    hipStream_t side = nullptr;        // default priority, non-blocking: carries branches that do not depend on each other
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> layer_ev;
     // Captured kernel sequences, keyed by (batch, wave-priority flag); a key is captured on its second
     // use, after one eager pass has set the kernels' attributes outside of any capture.
