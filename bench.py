@@ -14,6 +14,8 @@ input already sits in device memory.  Prints ONE JSON line:
                 are kept out of the pass `value` is taken from)
   cpu_baseline  the CPU oracle's ResNet-50 forward timed on this host on a bounded sample
   by_batch      images/s at the other batch sizes of the workload (1, 8, 32), shorter runs
+  two_instances images/s when the same K steps are issued alternately to two instances of the model on
+                the two compute streams (the paper's servers run several instances at once); not `value`
 """
 from __future__ import annotations
 
@@ -205,6 +207,25 @@ def main() -> int:
         out["by_batch"] = by
 
     model.free()
+
+    if not args.no_by_batch:
+        # the same K steps, alternately on two instances (high- and low-priority stream): what one GPU serves
+        # when two batches are in flight, as in the paper's instance pools
+        pair = ctx.load(blob, max_batch=B, n_instances=2)
+        for inst, pr in ((0, strait.PRIO_HIGH), (1, strait.PRIO_LOW)):
+            pair.copy_in(inst, pr, x)
+            pair.sync(inst, pr)
+        for _ in range(W):
+            pair.run(0, strait.PRIO_HIGH, B)
+            pair.run(1, strait.PRIO_LOW, B)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            pair.run(k & 1, strait.PRIO_HIGH if (k & 1) == 0 else strait.PRIO_LOW, B)
+        torch.cuda.synchronize()
+        out["two_instances"] = {"images_per_s": round(K * B / (time.perf_counter() - t0), 1), "steps": K,
+                                "note": "K steps alternating between two instances on two streams"}
+        pair.free()
 
     if args.colocation_seconds > 0:
         out["colocation"] = colocation(ctx, md, blob, args.colocation_seconds)
