@@ -225,6 +225,29 @@ def main() -> int:
         torch.cuda.synchronize()
         out["two_instances"] = {"images_per_s": round(K * B / (time.perf_counter() - t0), 1), "steps": K,
                                 "note": "K steps alternating between two instances on two streams"}
+        # end to end: the batch waits in pinned host memory; submit -> H2D on a copy stream -> kernels -> D2H, two
+        # instances double-buffering (the copy of one batch runs beside the kernels of the other)
+        stage = [pair.staging(i, B) for i in range(2)]
+        outs = [pair.new_output(B) for _ in range(2)]
+        for i in range(2):
+            stage[i][:] = x
+        tickets = [None, None]
+        def submit_e2e(k):
+            i = k & 1
+            if tickets[i] is not None:
+                pair.wait(tickets[i])
+            tickets[i] = pair.submit(strait.PRIO_HIGH if i == 0 else strait.PRIO_LOW, stage[i], None, outs[i])
+        for k in range(4):
+            submit_e2e(k)
+        for i in range(2):
+            pair.wait(tickets[i]); tickets[i] = None
+        t0 = time.perf_counter()
+        for k in range(K):
+            submit_e2e(k)
+        for i in range(2):
+            pair.wait(tickets[i]); tickets[i] = None
+        out["end_to_end"] = {"images_per_s": round(K * B / (time.perf_counter() - t0), 1), "steps": K,
+                             "note": "pinned host input -> H2D -> kernels -> D2H through strait_submit, two instances double-buffering"}
         pair.free()
 
     if args.colocation_seconds > 0:

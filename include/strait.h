@@ -143,11 +143,19 @@ strait_status strait_model_io(const strait_model* m, int32_t batch, size_t* in_b
 strait_status strait_model_info(const strait_model* m, int32_t* arch, int32_t* n_layers,
                                 int32_t* max_batch, int32_t* n_instances, int32_t hyper[8]);
 strait_status strait_model_layer(const strait_model* m, int32_t layer, strait_layer_info* out);
+/* The pinned input buffer of one instance (Section 3.2 step (1): "input data is written to pinned host
+ * memory"): a producer may write a batch there directly; strait_submit given this very pointer uses that
+ * instance and skips its own copy into pinned memory.  capacity = bytes of a max_batch input.  The buffer
+ * belongs to the library and must not be written while a batch submitted from it is in flight. */
+strait_status strait_model_staging(const strait_model* m, int32_t instance, void** host_in, size_t* capacity);
 
 /* Submit a batch at a priority level: picks an idle instance (E_BUSY if none -- never blocks),
  * copies `host_in` into the instance's pinned buffer, enqueues H2D copy, kernel sequence and
  * D2H copy without any host synchronisation, and returns a ticket.  `host_in` may be reused
  * as soon as the call returns; `host_out` must stay valid until strait_wait returns.
+ * If `host_in` is the staging buffer of an instance (strait_model_staging), that instance is the one
+ * used (E_BUSY if it is not idle) and the data are taken from there without a host copy; they must
+ * then stay untouched until strait_wait returns.
  * `valid_len` (host, int32[batch]) is required for the encoder and ignored otherwise. */
 strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch, const void* host_in,
                             const int32_t* valid_len, void* host_out, strait_ticket* ticket);

@@ -72,6 +72,7 @@ _SIGS = {
     "strait_model_free": (_i32, [_vp]),
     "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
     "strait_model_info": (_i32, [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32 * 8)]),
+    "strait_model_staging": (_i32, [_vp, _i32, C.POINTER(_vp), C.POINTER(_sz)]),
     "strait_model_layer": (_i32, [_vp, _i32, C.POINTER(LayerInfo)]),
     "strait_submit": (_i32, [_vp, _i32, _i32, _vp, _vp, _vp, C.POINTER(_vp)]),
     "strait_poll": (_i32, [_vp, C.POINTER(_i32)]),
@@ -220,6 +221,20 @@ class Model:
                 "top1": out[8 * n:8 * n + 4 * batch].view(np.int32)}
 
     # ---- the served path
+    def staging(self, instance: int, batch: int) -> np.ndarray:
+        """The instance's pinned input buffer as an fp16 array shaped like a batch of `batch` inputs; submit() given
+        this array uses that instance without copying."""
+        ptr, cap = _vp(), _sz()
+        _check(lib.strait_model_staging(self.handle, instance, C.byref(ptr), C.byref(cap)))
+        nbytes = self.io_bytes(batch)[0]
+        buf = (C.c_char * nbytes).from_address(ptr.value)
+        a = np.frombuffer(buf, dtype=np.float16)
+        if self.arch == 3:
+            _, hidden, _, _, seq = self.hyper[:5]
+            return a.reshape(batch, seq, hidden)
+        h, w, c = self.hyper[:3]
+        return a.reshape(batch, h, w, c)
+
     def submit(self, prio: int, x: np.ndarray, valid_len: Optional[np.ndarray], out: np.ndarray) -> int:
         batch = x.shape[0]
         assert x.dtype == np.float16 and x.flags.c_contiguous and out.flags.c_contiguous

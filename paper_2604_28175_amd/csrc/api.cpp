@@ -273,6 +273,14 @@ strait_status strait_model_info(const strait_model* m, int32_t* arch, int32_t* n
     return STRAIT_OK;
 }
 
+strait_status strait_model_staging(const strait_model* m, int32_t instance, void** host_in, size_t* capacity) {
+    if (!m || !host_in) { set_error("model_staging: null"); return STRAIT_E_INVALID; }
+    if (instance < 0 || instance >= (int)m->inst.size()) { set_error("instance %d outside 0..%zu", instance, m->inst.size() - 1); return STRAIT_E_INVALID; }
+    *host_in = m->inst[instance].pinned_in;
+    if (capacity) *capacity = m->in_bytes(m->max_batch);
+    return STRAIT_OK;
+}
+
 strait_status strait_model_layer(const strait_model* m, int32_t layer, strait_layer_info* out) {
     if (!m || !out) { set_error("model_layer: null"); return STRAIT_E_INVALID; }
     if (layer < 0 || layer >= (int)m->ops.size()) { set_error("layer %d outside 0..%zu", layer, m->ops.size() - 1); return STRAIT_E_INVALID; }
@@ -303,7 +311,7 @@ static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* hos
     Context* c = m->ctx;
     hipStream_t cs = c->copy[ci];
     const size_t inb = m->in_bytes(batch);
-    memcpy(in.pinned_in, host_in, inb);
+    if (host_in != in.pinned_in) memcpy(in.pinned_in, host_in, inb);
     int32_t* pv = nullptr;
     if (m->arch == STRAIT_ARCH_ENCODER) {
         const size_t off = (m->in_bytes(m->max_batch) + 255) / 256 * 256;
@@ -329,8 +337,16 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
     int idx = -1;
     {
         std::lock_guard<std::mutex> lk(m->mu);
+        int staged = -1;                              // input already in an instance's pinned buffer?
         for (size_t i = 0; i < m->inst.size(); ++i)
-            if (!m->inst[i].busy) { idx = (int)i; break; }
+            if (host_in == m->inst[i].pinned_in) staged = (int)i;
+        if (staged >= 0) {
+            if (m->inst[staged].busy) { set_error("submit: instance %d, whose staging buffer was given, is busy", staged); return STRAIT_E_BUSY; }
+            idx = staged;
+        } else {
+            for (size_t i = 0; i < m->inst.size(); ++i)
+                if (!m->inst[i].busy) { idx = (int)i; break; }
+        }
         if (idx < 0) { set_error("submit: all %zu instances busy", m->inst.size()); return STRAIT_E_BUSY; }
         m->inst[idx].busy = true;
         m->in_flight++;

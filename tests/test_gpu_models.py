@@ -187,3 +187,25 @@ def test_small_batch_split_reduction_is_reproducible(ctx):
         check_logits(m.decode(outs[0], 2)["logits"], ref.logits, m.decode(outs[0], 2)["top1"], "ResNet-50 64px b2 (split reductions)")
     finally:
         m.free()
+
+
+def test_submit_from_the_staging_buffer_makes_no_host_copy_and_gives_the_same_result(ctx):
+    S = ctx.S
+    md = synth.resnet50(4, hw=64)
+    x = synth.default_image_batch(md, 3, 5)
+    m = ctx.load(synth.pack(md), max_batch=4, n_instances=2)
+    try:
+        ref = m.new_output(3)
+        m.wait(m.submit(S.PRIO_LOW, x, None, ref))
+        st = m.staging(1, 3)                        # instance 1's pinned input buffer
+        st[:] = x
+        out = m.new_output(3)
+        rec = m.wait(m.submit(S.PRIO_HIGH, st, None, out))
+        assert rec.instance == 1 and np.array_equal(out, ref)
+        t = m.submit(S.PRIO_HIGH, st, None, out)    # the same buffer again while its batch is in flight: refused, not queued
+        with pytest.raises(S.StraitError) as e:
+            m.submit(S.PRIO_HIGH, st, None, m.new_output(3))
+        assert e.value.status == S.E_BUSY
+        m.wait(t)
+    finally:
+        m.free()
