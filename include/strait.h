@@ -349,6 +349,89 @@ strait_status strait_sched_complete(strait_sched* s, int32_t gpu, uint64_t runni
                                     double kernel_ns, int64_t h2d_end_ns, strait_completion* out);
 strait_status strait_sched_get_params(strait_sched* s, strait_intf_params* out);
 
+/* ---- offline profile of one (model, batch size) (needs the GPU) --------------------------------
+ * Section 3.2: the scheduler works from profiled p95 isolated latencies and from a batch's resource
+ * demand, the time-weighted average throughput of its kernels.  Runs `reps` (>= 1) batches of size `batch`
+ * alone on the GPU through strait_submit (the model must be otherwise idle) and fills `out`: nearest-rank
+ * p95 of enqueue-to-result latency, of the input copy and of the kernel sequence; the demand vector
+ * [LDS, L2, HBM, matrix pipes, vector pipes] as fractions of the chip's peaks, from the layer accounting
+ * (strait_model_layer) over the p95 kernel time: HBM = activation + weight bytes against 8 TB/s; matrix =
+ * 2 x MACs of the MFMA layers against 2.5 PFLOP/s; vector = depthwise MACs x 2 plus one operation per
+ * element of the other layers against 157.3 TFLOP/s; L2 = operand bytes of a 128 x 128-tiled product (each
+ * operand re-read once per tile row / column) plus the other layers' bytes against 64 B/clock/CU; LDS =
+ * three times the MFMA layers' operand bytes (written once, read by two waves) against 128 B/clock/CU.
+ * m_self_cmp is the matrix entry and m_self_mem the L2 entry (the two the paper selects). */
+strait_status strait_model_profile(strait_model* m, strait_priority prio, int32_t batch, int32_t reps,
+                                   strait_batch_profile* out);
+
+/* ---- serving front end ---------------------------------------------------------------------------
+ * Section 3 (system workflow), Section 4 and Section 5.1 of the paper.  A request enters the task queue
+ * of its model.  A queue asks for a decision once it holds max_batch requests or its oldest request has
+ * waited the model's batch formation timeout.  One scheduling thread visits the queues that ask, high
+ * priority first and first come first served within a level, and takes one decision per visit
+ * (strait_sched_decide): the requests the decision drops leave as violations, the chosen ones are gathered
+ * into the pinned buffer of a free instance and submitted as one batch on the stream of the model's
+ * priority; a queue whose batch is deferred (no capacity, no free instance, or the concurrency limit
+ * reached) is visited again after the next completion, the next arrival or `retry_ns`.  Execution threads
+ * wait for the batches, give every request its slice of the output and feed the measured kernel latency
+ * and transfer time back (strait_sched_complete).  A request's latency runs from strait_server_request to
+ * its result being in host memory; a dropped request counts as a deadline violation.
+ * The scheduler given to a server must have been created for one GPU and have the profile of every
+ * model added here; the server must be the only user of these models while it runs. */
+typedef struct strait_server strait_server;
+typedef struct strait_server_model {
+    strait_model* model;                       /* NULL only with a caller-supplied executor             */
+    int32_t model_id;                          /* the id its profile table is registered under          */
+    int32_t priority;                          /* strait_priority                                       */
+    int32_t max_batch;                         /* Section 5.1 uses 8                                    */
+    int32_t n_instances;                       /* batches of this model in flight at once; 0 = the model's instances */
+    int64_t deadline_ns;                       /* relative deadline of every request                    */
+    int64_t formation_timeout_ns;              /* how long the oldest request waits for company         */
+} strait_server_model;
+/* What runs a batch when it is not the library itself (host-side tests, simulations).  submit starts batch
+ * `batch_seq` and returns at once; wait blocks until it is complete and reports the measured kernel latency
+ * and input transfer time in ns.  Both are called from the server's threads; nonzero return = failure. */
+typedef struct strait_executor {
+    void* user;
+    int32_t (*submit)(void* user, uint64_t batch_seq, int32_t model_id, int32_t priority, int32_t batch,
+                      const void* const* inputs, void* const* outputs, const int32_t* valid_len);
+    int32_t (*wait)(void* user, uint64_t batch_seq, double* kernel_ns, double* h2d_ns);
+} strait_executor;
+typedef struct strait_request_record {
+    uint64_t request_id;
+    uint64_t batch_seq;                        /* running number of the batch it rode in, 0 if none    */
+    int32_t model_id, priority;
+    int32_t status;                            /* 0 served, 1 dropped early, 2 executor failure, 3 still queued at stop */
+    int32_t batch;                             /* size of that batch                                   */
+    int32_t position;                          /* its index in the batch (arrival order)               */
+    int32_t violated;                          /* result later than the deadline, or no result         */
+    int64_t t_enqueue_ns, t_dispatch_ns, t_done_ns, deadline_ns;   /* host CLOCK_MONOTONIC; deadline absolute */
+    double t_inf_pred_ns;                      /* Eq. 1 estimate at dispatch                            */
+    double kernel_ns, h2d_ns;                  /* measured, of its batch                                */
+} strait_request_record;
+typedef struct strait_server_stats {
+    int64_t requests, served, dropped, failed, violated_high, violated_low, requests_high, requests_low;
+    int64_t batches, batched_requests, deferrals, max_in_flight;
+} strait_server_stats;
+/* concurrency: batches in flight at most (Section 5.1 uses 4); retry_ns > 0; executor NULL = the library. */
+strait_status strait_server_create(strait_sched* sched, int32_t concurrency, int64_t retry_ns,
+                                   const strait_executor* executor, strait_server** out);
+strait_status strait_server_add_model(strait_server* s, const strait_server_model* desc);   /* before start */
+strait_status strait_server_start(strait_server* s);
+/* Non-blocking, thread-safe.  host_in (one sample, the model's input layout) and host_out (one sample's
+ * output, the layout of strait_model_io at batch 1) must stay valid until the request's record has been
+ * produced.  valid_len: encoder only.  E_INVALID before start or after stop. */
+strait_status strait_server_request(strait_server* s, int32_t model_id, const void* host_in, int32_t valid_len,
+                                    void* host_out, uint64_t* request_id);
+/* Blocks until every queue is empty and no batch is in flight (E_BUSY after timeout_ns). */
+strait_status strait_server_wait_idle(strait_server* s, int64_t timeout_ns);
+/* Moves up to `capacity` finished records (oldest first) to `out`; *n = how many. */
+strait_status strait_server_results(strait_server* s, strait_request_record* out, int32_t capacity, int32_t* n);
+strait_status strait_server_get_stats(strait_server* s, strait_server_stats* out);
+/* Stops taking requests, lets the batches in flight finish, reports what is still queued with status 3. */
+strait_status strait_server_stop(strait_server* s);
+strait_status strait_server_destroy(strait_server* s);   /* stops first if needed */
+
 #ifdef __cplusplus
 }
 #endif

@@ -114,6 +114,16 @@ _SIGS = {
     "strait_sched_decide": (_i32, [_vp, _i32, _i64, _vp, _vp, _i32, _vp]),
     "strait_sched_complete": (_i32, [_vp, _i32, C.c_uint64, _i64, _f64, _i64, _vp]),
     "strait_sched_get_params": (_i32, [_vp, _vp]),
+    "strait_model_profile": (_i32, [_vp, _i32, _i32, _i32, _vp]),
+    "strait_server_create": (_i32, [_vp, _i32, _i64, _vp, C.POINTER(_vp)]),
+    "strait_server_add_model": (_i32, [_vp, _vp]),
+    "strait_server_start": (_i32, [_vp]),
+    "strait_server_request": (_i32, [_vp, _i32, _vp, _i32, _vp, C.POINTER(C.c_uint64)]),
+    "strait_server_wait_idle": (_i32, [_vp, _i64]),
+    "strait_server_results": (_i32, [_vp, _vp, _i32, C.POINTER(_i32)]),
+    "strait_server_get_stats": (_i32, [_vp, _vp]),
+    "strait_server_stop": (_i32, [_vp]),
+    "strait_server_destroy": (_i32, [_vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -557,4 +567,111 @@ class Scheduler:
     def close(self):
         if self.handle:
             _check(lib.strait_sched_destroy(self.handle))
+            self.handle = _vp()
+
+
+class ServerModel(C.Structure):
+    """strait_server_model."""
+    _fields_ = [("model", _vp), ("model_id", _i32), ("priority", _i32), ("max_batch", _i32), ("n_instances", _i32),
+                ("deadline_ns", _i64), ("formation_timeout_ns", _i64)]
+
+
+_EXEC_SUBMIT = C.CFUNCTYPE(_i32, _vp, C.c_uint64, _i32, _i32, _i32, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_i32))
+_EXEC_WAIT = C.CFUNCTYPE(_i32, _vp, C.c_uint64, C.POINTER(_f64), C.POINTER(_f64))
+
+
+class Executor(C.Structure):
+    """strait_executor."""
+    _fields_ = [("user", _vp), ("submit", _EXEC_SUBMIT), ("wait", _EXEC_WAIT)]
+
+
+class RequestRecord(C.Structure):
+    """strait_request_record."""
+    _fields_ = [("request_id", C.c_uint64), ("batch_seq", C.c_uint64), ("model_id", _i32), ("priority", _i32),
+                ("status", _i32), ("batch", _i32), ("position", _i32), ("violated", _i32),
+                ("t_enqueue_ns", _i64), ("t_dispatch_ns", _i64), ("t_done_ns", _i64), ("deadline_ns", _i64),
+                ("t_inf_pred_ns", _f64), ("kernel_ns", _f64), ("h2d_ns", _f64)]
+
+
+class ServerStats(C.Structure):
+    """strait_server_stats."""
+    _fields_ = [(n, _i64) for n in ("requests", "served", "dropped", "failed", "violated_high", "violated_low",
+                                    "requests_high", "requests_low", "batches", "batched_requests", "deferrals",
+                                    "max_in_flight")]
+
+
+def profile_model(model: "Model", prio: int, batch: int, reps: int = 30) -> BatchProfile:
+    out = BatchProfile()
+    _check(lib.strait_model_profile(model.handle, prio, batch, reps, C.cast(C.byref(out), _vp)))
+    return out
+
+
+class Server:
+    """strait_server: task queues, batch formation and the scheduling / execution threads."""
+
+    def __init__(self, sched: Scheduler, concurrency: int = 4, retry_ns: int = 200_000, submit=None, wait=None):
+        """submit(batch_seq, model_id, priority, batch) / wait(batch_seq) -> (kernel_ns, h2d_ns): a host-side
+        executor in place of the library's own (both or neither)."""
+        self.sched = sched
+        self.handle = _vp()
+        self._keep = {}
+        self._exec = None
+        if submit is not None:
+            def _s(user, seq, mid, prio, batch, ins, outs, valid):
+                return int(submit(seq, mid, prio, batch) or 0)
+
+            def _w(user, seq, k, h):
+                r = wait(seq)
+                if r is None:
+                    return 1
+                k[0], h[0] = float(r[0]), float(r[1])
+                return 0
+            self._exec = Executor(None, _EXEC_SUBMIT(_s), _EXEC_WAIT(_w))
+        _check(lib.strait_server_create(sched.handle, concurrency, retry_ns,
+                                        None if self._exec is None else C.cast(C.byref(self._exec), _vp), C.byref(self.handle)))
+
+    def add_model(self, model: Optional["Model"], model_id: int, priority: int, max_batch: int, deadline_ns: int,
+                  formation_timeout_ns: int, n_instances: int = 0):
+        d = ServerModel(None if model is None else model.handle, model_id, priority, max_batch, n_instances,
+                        deadline_ns, formation_timeout_ns)
+        _check(lib.strait_server_add_model(self.handle, C.cast(C.byref(d), _vp)))
+
+    def start(self):
+        _check(lib.strait_server_start(self.handle))
+
+    def request(self, model_id: int, x: Optional[np.ndarray], out: Optional[np.ndarray], valid_len: int = 0) -> int:
+        rid = C.c_uint64()
+        _check(lib.strait_server_request(self.handle, model_id, None if x is None else _np_ptr(x), valid_len,
+                                         None if out is None else _np_ptr(out), C.byref(rid)))
+        self._keep[rid.value] = (x, out)
+        return rid.value
+
+    def wait_idle(self, timeout_s: float = 30.0):
+        _check(lib.strait_server_wait_idle(self.handle, int(timeout_s * 1e9)))
+
+    def results(self, capacity: int = 4096):
+        """Finished request records, oldest first (everything available, in chunks of `capacity`)."""
+        out = []
+        arr = (RequestRecord * capacity)()
+        while True:
+            n = _i32()
+            _check(lib.strait_server_results(self.handle, C.cast(arr, _vp), capacity, C.byref(n)))
+            for i in range(n.value):
+                r = RequestRecord.from_buffer_copy(arr[i])
+                self._keep.pop(r.request_id, None)
+                out.append(r)
+            if n.value < capacity:
+                return out
+
+    def stats(self) -> ServerStats:
+        st = ServerStats()
+        _check(lib.strait_server_get_stats(self.handle, C.cast(C.byref(st), _vp)))
+        return st
+
+    def stop(self):
+        _check(lib.strait_server_stop(self.handle))
+
+    def close(self):
+        if self.handle:
+            _check(lib.strait_server_destroy(self.handle))
             self.handle = _vp()
