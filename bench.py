@@ -83,6 +83,53 @@ def colocation(ctx, md_resnet, blob_resnet, seconds):
     return res
 
 
+def serving(ctx, md_resnet, blob_resnet, seconds, hp_rate, lp_rate):
+    """The whole of the paper's system on one GPU: single requests for a high-priority ResNet-50 and a
+    low-priority MobileNetV2 on Poisson schedules through the front end (maximum batch 8, four batches in
+    flight, batch formation timeout a tenth of the deadline: Section 5.1), first the high-priority model
+    alone, then both."""
+    import synth
+    import paper_2604_28175_amd as strait
+    from paper_2604_28175_amd import serve
+
+    seed = synth.SEEDS["colocation"] + 7
+    hp = ctx.load(blob_resnet, max_batch=8, n_instances=4)
+    md_lp = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2])
+    lp = ctx.load(synth.pack(md_lp), max_batch=8, n_instances=4)
+    sched = strait.Scheduler(1)
+    prof = {1: serve.offline_profiles(hp, strait.PRIO_HIGH, 8), 2: serve.offline_profiles(lp, strait.PRIO_LOW, 8)}
+    sched.set_profile(1, strait.PRIO_HIGH, serve.profile_tuples(prof[1]))
+    sched.set_profile(2, strait.PRIO_LOW, serve.profile_tuples(prof[2]))
+    cfg = {1: dict(model=hp, prio=strait.PRIO_HIGH, rate=hp_rate, deadline_ms=5.0),
+           2: dict(model=lp, prio=strait.PRIO_LOW, rate=lp_rate, deadline_ms=25.0)}
+    xs = {1: list(synth.default_image_batch(md_resnet, 8, seed)), 2: list(synth.default_image_batch(md_lp, 8, seed + 1))}
+    res = {"hp": f"resnet50_v1.5, single requests, Poisson {hp_rate:.0f}/s, deadline 5 ms",
+           "lp": f"mobilenet_v2, single requests, Poisson {lp_rate:.0f}/s, deadline 25 ms",
+           "max_batch": 8, "concurrency": 4, "seconds_per_phase": seconds,
+           "profile_ms": {name: {"b1": [round(p[0].t_inf_isol_ns * 1e-6, 3), round(p[0].t_kernel_isol_ns * 1e-6, 3)],
+                                 "b8": [round(p[7].t_inf_isol_ns * 1e-6, 3), round(p[7].t_kernel_isol_ns * 1e-6, 3)],
+                                 "demand_b8": [round(v, 3) for v in p[7].m]} for name, p in (("hp", prof[1]), ("lp", prof[2]))}}
+    for phase, mids in (("hp_alone", (1,)), ("hp_and_lp", (1, 2))):
+        srv = strait.Server(sched, 4, 200_000)
+        for mid in mids:
+            c = cfg[mid]
+            srv.add_model(c["model"], mid, c["prio"], 8, int(c["deadline_ms"] * 1e6), int(c["deadline_ms"] * 1e5))
+        srv.start()
+        streams = {mid: {"model": cfg[mid]["model"], "inputs": xs[mid],
+                         "arrivals_ns": synth.poisson_arrivals_ns(seed + mid, cfg[mid]["rate"], seconds)} for mid in mids}
+        summ = serve.run_open_loop(srv, streams, seconds)
+        st = srv.stats()
+        srv.close()
+        res[phase] = {("hp" if mid == 1 else "lp"): summ[mid] for mid in mids}
+        res[phase]["batches"] = st.batches
+        res[phase]["max_in_flight"] = st.max_in_flight
+        res[phase]["deferrals"] = st.deferrals
+    sched.close()
+    hp.free()
+    lp.free()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +140,10 @@ def main() -> int:
     ap.add_argument("--no-by-batch", action="store_true")
     ap.add_argument("--colocation-seconds", type=float, default=5.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
+    ap.add_argument("--serving-seconds", type=float, default=3.0,
+                    help="seconds per phase of the request-level serving run (0 = skip)")
+    ap.add_argument("--serving-hp-rate", type=float, default=4000.0, help="high-priority requests per second")
+    ap.add_argument("--serving-lp-rate", type=float, default=10000.0, help="low-priority requests per second")
     ap.add_argument("--copy-calibration-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference for hardware byte counters)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="images the CPU oracle is timed on (0 = twelve per thread)")
@@ -252,6 +303,8 @@ def main() -> int:
 
     if args.colocation_seconds > 0:
         out["colocation"] = colocation(ctx, md, blob, args.colocation_seconds)
+    if args.serving_seconds > 0:
+        out["serving"] = serving(ctx, md, blob, args.serving_seconds, args.serving_hp_rate, args.serving_lp_rate)
     ctx.close()
 
     if not args.no_cpu_baseline:
