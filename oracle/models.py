@@ -1,4 +1,4 @@
-"""CPU oracle: forward passes of the four served architectures in fp64.
+"""CPU oracle: forward passes of the served architectures in fp64.
 
 TEST INFRASTRUCTURE ONLY (see ops.py).  Written from the public definitions of the
 architectures; the paper fixes the workload only as "a sequence of dependent kernels"
@@ -18,7 +18,7 @@ import numpy as np
 
 from . import ops
 
-ARCH_TINY_CNN, ARCH_RESNET50, ARCH_MOBILENETV2, ARCH_ENCODER = 0, 1, 2, 3
+ARCH_TINY_CNN, ARCH_RESNET50, ARCH_MOBILENETV2, ARCH_ENCODER, ARCH_VGG19, ARCH_VIT = 0, 1, 2, 3, 4, 5
 FP16_MAX = 65504.0
 
 
@@ -173,6 +173,75 @@ def encoder_forward(t, x, valid_len, hyper, keep=False) -> Result:
     return Result(y, None, ops.argmax_first(y[:, 0, :]), tr)
 
 
+VGG19_CFG = [64, 64, "M", 128, 128, "M", 256, 256, 256, 256, "M", 512, 512, 512, 512, "M", 512, 512, 512, 512, "M"]
+
+
+def vgg19_forward(t, x, keep=False) -> Result:
+    """VGG-19 (configuration E of the VGG paper, no normalisation; Table 1 of the served-model list gives
+    19.63 G multiply-accumulates): sixteen 3x3 convolutions with bias and ReLU, 2x2 max pooling of stride 2
+    after the 2nd, 4th, 8th, 12th and 16th, the feature map flattened channel-major (channel, row, column),
+    then FC-ReLU-FC-ReLU-FC and softmax."""
+    tr = Trace(keep=keep)
+    y = np.asarray(x, np.float64)
+    i = 0
+    for c in VGG19_CFG:
+        if c == "M":
+            y = ops.maxpool2d(y, 2, 2, 0)
+            tr.add(f"pool{i}", "pool", 0, y)
+        else:
+            y = _conv_unit(t, tr, f"conv{i}", y, 1, 1, "relu", bn=False)
+            i += 1
+    n = y.shape[0]
+    w1 = np.asarray(t["fc1.w"], np.float64)
+    flat = np.transpose(y, (0, 3, 1, 2)).reshape(n, -1)                 # [N, C*H*W]
+    f = ops.relu(ops.linear(flat, w1.reshape(w1.shape[0], -1), t["fc1.b"]))
+    tr.add("fc1", "fc", f.size * flat.shape[1], f)
+    g = ops.relu(ops.linear(f, t["fc2.w"], t["fc2.b"]))
+    tr.add("fc2", "fc", g.size * f.shape[1], g)
+    return _head(t, tr, g)
+
+
+def vit_forward(t, x, hyper, keep=False) -> Result:
+    """Vision Transformer ("An image is worth 16x16 words"), pre-LayerNorm blocks:
+         tokens = [cls ; patches W_p + b_p] + pos
+         z <- z + Attn(LN1(z)) W_o + b_o ;  z <- z + GELU(LN2(z) W_1 + b_1) W_2 + b_2      (per block)
+         logits = LN(z)[token 0] W_h + b_h.
+    A patch is a 16x16 window taken with stride 16, its values ordered as the weight tensor's (channel, row,
+    column); LayerNorm eps 1e-6; every key takes part in attention."""
+    layers, hidden, heads, ffn = hyper[4:8]
+    tr = Trace(keep=keep)
+    pw = t["patch.w"]
+    y = ops.conv2d(np.asarray(x, np.float64), pw, t["patch.b"].astype(np.float64), pw.shape[2], 0)
+    n, gh, gw, _ = y.shape
+    tr.add("patch", "conv", y.size * pw.shape[1] * pw.shape[2] * pw.shape[3], y)
+    tok = y.reshape(n, gh * gw, hidden)
+    cls = np.broadcast_to(np.asarray(t["cls"], np.float64), (n, 1, hidden))
+    z = np.concatenate([cls, tok], axis=1) + np.asarray(t["pos"], np.float64)[None]
+    tr.add("tokens", "add", 0, z)
+    seq = z.shape[1]
+    ntok = n * seq
+    full = np.full(n, seq, dtype=np.int32)
+    for i in range(layers):
+        p = f"l{i}"
+        h = ops.layernorm(z, t[p + ".ln1.g"], t[p + ".ln1.b"], eps=1e-6)
+        q = ops.linear(h, t[p + ".q.w"], t[p + ".q.b"])
+        k = ops.linear(h, t[p + ".k.w"], t[p + ".k.b"])
+        v = ops.linear(h, t[p + ".v.w"], t[p + ".v.b"])
+        tr.add(p + ".qkv", "gemm", 3 * ntok * hidden * hidden, np.concatenate([q, k, v], axis=-1))
+        a = ops.attention(q, k, v, full, heads)
+        tr.add(p + ".attn", "attention", 2 * n * seq * seq * hidden, a)
+        z = z + ops.linear(a, t[p + ".o.w"], t[p + ".o.b"])
+        tr.add(p + ".o", "gemm", ntok * hidden * hidden, z)
+        h = ops.layernorm(z, t[p + ".ln2.g"], t[p + ".ln2.b"], eps=1e-6)
+        f = ops.gelu(ops.linear(h, t[p + ".ffn1.w"], t[p + ".ffn1.b"]))
+        tr.add(p + ".ffn1", "gemm", ntok * hidden * ffn, f)
+        z = z + ops.linear(f, t[p + ".ffn2.w"], t[p + ".ffn2.b"])
+        tr.add(p + ".ffn2", "gemm", ntok * hidden * ffn, z)
+    feat = ops.layernorm(z[:, 0, :], t["ln.g"], t["ln.b"], eps=1e-6)
+    tr.add("ln", "norm", 0, feat)
+    return _head(t, tr, feat)
+
+
 def forward(arch, tensors, x, valid_len=None, hyper=None, keep=False) -> Result:
     if arch == ARCH_TINY_CNN:
         return tiny_cnn_forward(tensors, x, keep)
@@ -182,4 +251,8 @@ def forward(arch, tensors, x, valid_len=None, hyper=None, keep=False) -> Result:
         return mobilenet_v2_forward(tensors, x, keep)
     if arch == ARCH_ENCODER:
         return encoder_forward(tensors, x, valid_len, hyper, keep)
+    if arch == ARCH_VGG19:
+        return vgg19_forward(tensors, x, keep)
+    if arch == ARCH_VIT:
+        return vit_forward(tensors, x, hyper, keep)
     raise ValueError(arch)

@@ -21,6 +21,11 @@ Weight recipe
 * tiny CNN: no BatchNorm, explicit zero biases; FC biases are zero everywhere.
 * encoder: all matrices and biases N(0,0.02); LayerNorm gamma ~ U[0.8,1.2],
   beta ~ N(0,0.02).
+* VGG-19 (no BatchNorm): He-normal weights, biases N(0,0.02); the first fully connected layer is
+  stored [out, 512, h, w] so that the order in which the feature map is flattened (channel, row,
+  column) is part of the data.
+* ViT: every matrix, bias, the class token and the position embeddings N(0,0.02); LayerNorm as the
+  encoder's; hyper = (H, W, 3, classes, layers, hidden, heads, ffn), patches of 16 x 16.
 """
 from __future__ import annotations
 
@@ -36,15 +41,21 @@ ARCH_TINY_CNN = 0
 ARCH_RESNET50 = 1
 ARCH_MOBILENETV2 = 2
 ARCH_ENCODER = 3
+ARCH_VGG19 = 4
+ARCH_VIT = 5
 
 ARCH_NAMES = {ARCH_TINY_CNN: "tiny_cnn", ARCH_RESNET50: "resnet50_v1.5",
-              ARCH_MOBILENETV2: "mobilenet_v2", ARCH_ENCODER: "encoder"}
+              ARCH_MOBILENETV2: "mobilenet_v2", ARCH_ENCODER: "encoder",
+              ARCH_VGG19: "vgg19", ARCH_VIT: "vit_b16"}
 
 BN_EPS = 1e-5
 
 # MobileNetV2 width 1.0: (expansion t, output channels c, repeats n, first stride s)
 MOBILENETV2_CFG = [(1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2),
                    (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)]
+# VGG-19: output channels of the 3x3 convolutions, "M" = 2x2 max pooling with stride 2
+VGG19_CFG = [64, 64, "M", 128, 128, "M", 256, 256, 256, 256, "M", 512, 512, 512, 512, "M", 512, 512, 512, 512, "M"]
+VIT_PATCH = 16
 RESNET50_BLOCKS = [3, 4, 6, 3]
 RESNET50_PLANES = [64, 128, 256, 512]
 
@@ -167,9 +178,60 @@ def encoder(seed: int, layers: int = 12, hidden: int = 768, heads: int = 12, ffn
     return md
 
 
+def vgg19(seed: int, hw: int = 224, classes: int = 1000, fc: int = 4096) -> ModelData:
+    assert hw % 32 == 0
+    md = ModelData(ARCH_VGG19, (hw, hw, 3, classes, fc))
+    g = _Gen(seed, md)
+    cin, i = 3, 0
+    for c in VGG19_CFG:
+        if c == "M":
+            continue
+        g.he(f"conv{i}.w", (c, cin, 3, 3))
+        g.normal(f"conv{i}.b", (c,), 0.02)
+        cin, i = c, i + 1
+    f = hw // 32
+    g.he("fc1.w", (fc, cin, f, f))
+    g.normal("fc1.b", (fc,), 0.02)
+    g.he("fc2.w", (fc, fc))
+    g.normal("fc2.b", (fc,), 0.02)
+    g.he("fc.w", (classes, fc))
+    g.normal("fc.b", (classes,), 0.02)
+    return md
+
+
+def vit(seed: int, hw: int = 224, classes: int = 1000, layers: int = 12, hidden: int = 768, heads: int = 12,
+        ffn: int = 3072) -> ModelData:
+    assert hw % VIT_PATCH == 0
+    md = ModelData(ARCH_VIT, (hw, hw, 3, classes, layers, hidden, heads, ffn))
+    g = _Gen(seed, md)
+    n_tok = (hw // VIT_PATCH) ** 2 + 1
+    g.normal("patch.w", (hidden, 3, VIT_PATCH, VIT_PATCH), 0.02)
+    g.normal("patch.b", (hidden,), 0.02)
+    g.normal("cls", (hidden,), 0.02)
+    g.normal("pos", (n_tok, hidden), 0.02)
+    for i in range(layers):
+        p = f"l{i}"
+        g.uniform(f"{p}.ln1.g", (hidden,), 0.8, 1.2)
+        g.normal(f"{p}.ln1.b", (hidden,), 0.02)
+        for nm in ("q", "k", "v", "o"):
+            g.normal(f"{p}.{nm}.w", (hidden, hidden), 0.02)
+            g.normal(f"{p}.{nm}.b", (hidden,), 0.02)
+        g.uniform(f"{p}.ln2.g", (hidden,), 0.8, 1.2)
+        g.normal(f"{p}.ln2.b", (hidden,), 0.02)
+        g.normal(f"{p}.ffn1.w", (ffn, hidden), 0.02)
+        g.normal(f"{p}.ffn1.b", (ffn,), 0.02)
+        g.normal(f"{p}.ffn2.w", (hidden, ffn), 0.02)
+        g.normal(f"{p}.ffn2.b", (hidden,), 0.02)
+    g.uniform("ln.g", (hidden,), 0.8, 1.2)
+    g.normal("ln.b", (hidden,), 0.02)
+    g.normal("fc.w", (classes, hidden), 0.02)
+    g.normal("fc.b", (classes,), 0.02)
+    return md
+
+
 def make_model(arch: int, seed: int, **kw) -> ModelData:
-    return {ARCH_TINY_CNN: tiny_cnn, ARCH_RESNET50: resnet50,
-            ARCH_MOBILENETV2: mobilenet_v2, ARCH_ENCODER: encoder}[arch](seed, **kw)
+    return {ARCH_TINY_CNN: tiny_cnn, ARCH_RESNET50: resnet50, ARCH_MOBILENETV2: mobilenet_v2,
+            ARCH_ENCODER: encoder, ARCH_VGG19: vgg19, ARCH_VIT: vit}[arch](seed, **kw)
 
 
 # ----------------------------------------------------------------------------
@@ -178,7 +240,7 @@ def make_model(arch: int, seed: int, **kw) -> ModelData:
 
 def image_batch(md: ModelData, batch: int, seed: int, dist: str = "normal") -> np.ndarray:
     """fp16 NHWC batch: N(0,1) (ResNet-50, MobileNetV2) or U[0,1) (tiny CNN)."""
-    h, w, c, _ = md.hyper
+    h, w, c = md.hyper[:3]
     n = batch * h * w * c
     name = f"input.b{batch}"
     x = rng.normal(seed, name, n) if dist == "normal" else rng.uniform(seed, name, n)

@@ -183,3 +183,131 @@ def test_encoder_mask_invariance_and_single_layer_composition():
     g, be = t["l1.ln2.g"].astype(np.float64), t["l1.ln2.b"].astype(np.float64)
     z = (r.logits - be) / g
     assert np.abs(z.mean(-1)).max() < 1e-9 and np.abs(z.var(-1) - 1).max() < 1e-6
+
+
+# ------------------------------------------------------------------ VGG-19
+def test_vgg19_topology_matches_table1():
+    md = synth.vgg19(synth.SEEDS[synth.ARCH_VGG19])
+    x = synth.default_image_batch(md, 1, 11)
+    r = models.vgg19_forward(md.tensors, x)
+    tr = r.trace
+    assert round(tr.total_macs / 1e9, 2) == _table1()["vgg19"]              # Table 1: 19.63
+    assert tr.n_kind("conv") == 16 and tr.n_kind("pool") == 5 and tr.n_kind("fc") == 3
+    assert md.n_params() == 143_667_240                                      # the published parameter count
+    shapes = {l.name: l.out_shape for l in tr.layers}
+    assert shapes["conv1"] == (1, 224, 224, 64) and shapes["pool2"] == (1, 112, 112, 64)
+    assert shapes["conv15"] == (1, 14, 14, 512) and shapes["pool16"] == (1, 7, 7, 512) and shapes["fc1"] == (1, 4096)
+    assert max(l.max_abs for l in tr.layers) < 6e4
+
+
+def test_vgg19_against_independent_composition():
+    """The whole small network again from windows, reshape-max pooling and matrix products."""
+    md = synth.vgg19(5, hw=64, classes=10, fc=24)
+    x = synth.default_image_batch(md, 2, 6)
+    r = models.vgg19_forward(md.tensors, x, keep=True)
+    t = md.tensors
+    y = np.asarray(x, np.float64)
+    i = 0
+    for c in synth.models.VGG19_CFG:
+        if c == "M":
+            n, h, w, ch = y.shape
+            y = y.reshape(n, h // 2, 2, w // 2, 2, ch).max(axis=(2, 4))
+        else:
+            y = np.maximum(conv_by_windows(y, t[f"conv{i}.w"], t[f"conv{i}.b"].astype(np.float64), 1, 1), 0)
+            i += 1
+    assert y.shape == (2, 2, 2, 512) and np.allclose(y, r.trace.acts["pool16"], rtol=1e-9, atol=1e-9)
+    # channel-major flattening: feature (c, h, w) meets fc1.w[:, c, h, w]
+    f = np.maximum(np.einsum("nhwc,ochw->no", y, t["fc1.w"].astype(np.float64)) + t["fc1.b"].astype(np.float64), 0)
+    g = np.maximum(f @ t["fc2.w"].astype(np.float64).T + t["fc2.b"].astype(np.float64), 0)
+    logits = g @ t["fc.w"].astype(np.float64).T + t["fc.b"].astype(np.float64)
+    assert np.allclose(logits, r.logits, rtol=1e-9, atol=1e-9)
+
+
+def test_vgg19_flatten_order_is_channel_row_column():
+    md = synth.vgg19(5, hw=64, classes=4, fc=8)
+    t = dict(md.tensors)
+    pick = [(0, 0, 0), (3, 0, 1), (7, 1, 0), (500, 1, 1), (511, 0, 1), (100, 1, 0), (1, 1, 1), (256, 0, 0)]
+    w1 = np.zeros_like(t["fc1.w"])
+    for j, (c, h, w) in enumerate(pick):
+        w1[j, c, h, w] = 1
+    t["fc1.w"], t["fc1.b"] = w1, np.zeros_like(t["fc1.b"])
+    x = synth.default_image_batch(md, 1, 2)
+    r = models.vgg19_forward(t, x, keep=True)
+    feat = r.trace.acts["pool16"]
+    assert np.array_equal(r.trace.acts["fc1"][0], [max(feat[0, h, w, c], 0.0) for c, h, w in pick])
+
+
+# ------------------------------------------------------------------ ViT
+def test_vit_topology_matches_table1():
+    md = synth.vit(synth.SEEDS[synth.ARCH_VIT])
+    x = synth.default_image_batch(md, 1, 11)
+    r = models.vit_forward(md.tensors, x, md.hyper)
+    tr = r.trace
+    attn = sum(l.macs for l in tr.layers if l.kind == "attention")
+    assert round((tr.total_macs - attn) / 1e9, 2) == _table1()["vit_b16"]   # Table 1: 16.85
+    assert round(tr.total_macs / 1e9, 2) == _table1()["vit_b16_with_attention_products"]
+    assert md.n_params() == 86_567_656                                      # the published parameter count
+    shapes = {l.name: l.out_shape for l in tr.layers}
+    assert shapes["patch"] == (1, 14, 14, 768) and shapes["tokens"] == (1, 197, 768) and shapes["l11.ffn2"] == (1, 197, 768)
+    assert r.logits.shape == (1, 1000) and max(l.max_abs for l in tr.layers) < 6e4
+
+
+def small_vit():
+    md = synth.vit(9, hw=48, classes=7, layers=2, hidden=32, heads=2, ffn=64)
+    return md, synth.default_image_batch(md, 3, 4)
+
+
+def test_vit_patches_and_tokens():
+    md, x = small_vit()
+    t = md.tensors
+    r = models.vit_forward(t, x, md.hyper, keep=True)
+    n, g = 3, 3
+    patches = np.asarray(x, np.float64).reshape(n, g, 16, g, 16, 3).transpose(0, 1, 3, 5, 2, 4).reshape(n, g * g, 3 * 256)
+    emb = patches @ t["patch.w"].astype(np.float64).reshape(32, -1).T + t["patch.b"].astype(np.float64)
+    z = r.trace.acts["tokens"]
+    pos = t["pos"].astype(np.float64)
+    assert z.shape == (n, 10, 32)
+    assert np.allclose(z[:, 1:], emb + pos[1:], rtol=1e-10, atol=1e-12)
+    assert np.allclose(z[:, 0], t["cls"].astype(np.float64) + pos[0], rtol=0, atol=0)
+
+
+def test_vit_block_matches_the_library_pre_norm_layer():
+    """torch.nn.TransformerEncoderLayer(norm_first=True, activation='gelu') is the same block."""
+    import torch
+    md, x = small_vit()
+    t = md.tensors
+    r = models.vit_forward(t, x, md.hyper, keep=True)
+    layer = torch.nn.TransformerEncoderLayer(32, 2, 64, dropout=0.0, activation="gelu", layer_norm_eps=1e-6,
+                                             batch_first=True, norm_first=True).double().eval()
+    z = torch.from_numpy(r.trace.acts["tokens"])
+    for i in range(2):
+        p = f"l{i}"
+        f64 = lambda k: torch.from_numpy(t[k].astype(np.float64))
+        sd = {"self_attn.in_proj_weight": torch.cat([f64(p + ".q.w"), f64(p + ".k.w"), f64(p + ".v.w")]),
+              "self_attn.in_proj_bias": torch.cat([f64(p + ".q.b"), f64(p + ".k.b"), f64(p + ".v.b")]),
+              "self_attn.out_proj.weight": f64(p + ".o.w"), "self_attn.out_proj.bias": f64(p + ".o.b"),
+              "linear1.weight": f64(p + ".ffn1.w"), "linear1.bias": f64(p + ".ffn1.b"),
+              "linear2.weight": f64(p + ".ffn2.w"), "linear2.bias": f64(p + ".ffn2.b"),
+              "norm1.weight": f64(p + ".ln1.g"), "norm1.bias": f64(p + ".ln1.b"),
+              "norm2.weight": f64(p + ".ln2.g"), "norm2.bias": f64(p + ".ln2.b")}
+        layer.load_state_dict(sd)
+        with torch.no_grad():
+            z = layer(z)
+        assert np.allclose(z.numpy(), r.trace.acts[p + ".ffn2"], rtol=1e-9, atol=1e-11)
+
+
+def test_vit_head_reads_the_class_token_after_the_final_norm():
+    md, x = small_vit()
+    t = dict(md.tensors)
+    for i in range(2):                                                 # blocks that add nothing: tokens pass through
+        for k in (f"l{i}.o.w", f"l{i}.o.b", f"l{i}.ffn2.w", f"l{i}.ffn2.b"):
+            t[k] = np.zeros_like(t[k])
+    r = models.vit_forward(t, x, md.hyper)
+    c = t["cls"].astype(np.float64) + t["pos"][0].astype(np.float64)
+    n = (c - c.mean()) / np.sqrt(c.var() + 1e-6) * t["ln.g"].astype(np.float64) + t["ln.b"].astype(np.float64)
+    want = n @ t["fc.w"].astype(np.float64).T + t["fc.b"].astype(np.float64)
+    assert np.allclose(r.logits, want[None], rtol=1e-10, atol=1e-12)    # the same for every image
+    full = models.vit_forward(md.tensors, x, md.hyper)
+    assert np.abs(full.logits - full.logits[0]).max() > 1e-6          # ... and not with the real blocks
+    one = models.vit_forward(md.tensors, x[1:2], md.hyper)
+    assert np.allclose(one.logits[0], full.logits[1], rtol=1e-12, atol=1e-12)
