@@ -50,7 +50,10 @@ typedef enum {
     STRAIT_ARCH_TINY_CNN = 0,      /* conv3x3 x3 + GAP + FC + softmax                        */
     STRAIT_ARCH_RESNET50 = 1,      /* ResNet-50 v1.5, BatchNorm folded at load               */
     STRAIT_ARCH_MOBILENETV2 = 2,   /* MobileNetV2 1.0                                        */
-    STRAIT_ARCH_ENCODER = 3        /* post-LayerNorm Transformer encoder stack               */
+    STRAIT_ARCH_ENCODER = 3,       /* post-LayerNorm Transformer encoder stack               */
+    STRAIT_ARCH_VGG19 = 4,         /* VGG-19 (configuration E, no normalisation); hyper = {H, W, 3, classes, fc width} */
+    STRAIT_ARCH_VIT = 5            /* Vision Transformer, 16x16 patches, pre-LayerNorm blocks; hyper = {H, W, 3,
+                                      classes, layers, hidden, heads, ffn}; input and output as the CNNs'      */
 } strait_arch;
 
 typedef enum { STRAIT_ACT_NONE = 0, STRAIT_ACT_RELU = 1, STRAIT_ACT_RELU6 = 2, STRAIT_ACT_GELU = 3 } strait_act;
@@ -202,6 +205,13 @@ strait_status strait_k_gemm(void* stream, const void* x, const void* w, const fl
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,
                                  int32_t hp);
+/* Max pooling 2x2, stride 2, no padding; C % 8 == 0, H and W even. */
+strait_status strait_k_maxpool2x2s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
+                                    void* y, int32_t hp);
+/* Token assembly of a Vision Transformer: z[n][0] = cls + pos[0], z[n][1+t] = patch[n][t] + pos[1+t];
+ * patch fp16 [N][T][D], cls fp32 [D], pos fp32 [T+1][D], z fp16 [N][T+1][D]; D % 8 == 0. */
+strait_status strait_k_vit_tokens(void* stream, const void* patch, const float* cls, const float* pos, int32_t N,
+                                  int32_t T, int32_t D, void* z, int32_t hp);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins); C % 8 == 0. */
 strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                     void* y, int32_t hp);
@@ -217,8 +227,8 @@ strait_status strait_k_softmax_top1(void* stream, const float* logits, int32_t r
 strait_status strait_k_layernorm(void* stream, const void* x, const float* gamma, const float* beta,
                                  int32_t rows, int32_t n, float eps, void* y, int32_t hp);
 /* Fused masked multi-head attention.  qkv fp16 [B][S][3*hidden] (Q | K | V along the last
- * axis), valid_len int32 [B] (device), out fp16 [B][S][hidden]; head dim must be 64, S <= 128
- * and S % 32 == 0.  Keys j >= valid_len[b] get probability exactly 0; query rows in 32-row
+ * axis), valid_len int32 [B] (device), out fp16 [B][S][hidden]; head dim must be 64,
+ * 1 <= S <= 256.  Keys j >= valid_len[b] get probability exactly 0; query rows in 32-row
  * blocks that lie entirely at or beyond valid_len[b] are written as zeros. */
 strait_status strait_k_attention(void* stream, const void* qkv, const int32_t* valid_len, int32_t B, int32_t S,
                                  int32_t heads, void* out, int32_t hp);

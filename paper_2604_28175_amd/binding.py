@@ -87,6 +87,8 @@ _SIGS = {
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_maxpool2x2s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_vit_tokens": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_global_avgpool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_softmax_top1": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp, _i32]),
     "strait_k_layernorm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, C.c_float, _vp, _i32]),
@@ -359,6 +361,22 @@ def k_maxpool3x3s2(x, hp=0, stream=None):
     y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=torch.float16, device=x.device)
     _check(lib.strait_k_maxpool3x3s2(_stream(stream), _dev(x), n, h, w, c, _dev(y), hp))
     return y
+
+
+def k_maxpool2x2s2(x, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    y = torch.empty((n, h // 2, w // 2, c), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_maxpool2x2s2(_stream(stream), _dev(x), n, h, w, c, _dev(y), hp))
+    return y
+
+
+def k_vit_tokens(patch, cls, pos, hp=0, stream=None):
+    import torch
+    n, t, d = patch.shape
+    z = torch.empty((n, t + 1, d), dtype=torch.float16, device=patch.device)
+    _check(lib.strait_k_vit_tokens(_stream(stream), _dev(patch), _dev(cls), _dev(pos), n, t, d, _dev(z), hp))
+    return z
 
 
 def k_global_avgpool(x, hp=0, stream=None):

@@ -224,7 +224,7 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
             return STRAIT_E_NOMEM;
         }
         // valid lengths default to the full sequence
-        if (m->arch == STRAIT_ARCH_ENCODER) {
+        if (m->arch == STRAIT_ARCH_ENCODER || m->arch == STRAIT_ARCH_VIT) {
             std::vector<int32_t> full(d->max_batch, m->seq);
             HIP_TRY(hipMemcpy(in.dev_valid, full.data(), full.size() * 4, hipMemcpyHostToDevice));
         }
@@ -564,6 +564,13 @@ strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t
 }
 strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
     return launch_maxpool3x3s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_maxpool2x2s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
+    return launch_maxpool2x2s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_vit_tokens(void* stream, const void* patch, const float* cls, const float* pos, int32_t N, int32_t T,
+                                  int32_t D, void* z, int32_t hp) {
+    return launch_vit_tokens((const half_t*)patch, cls, pos, N, T, D, (half_t*)z, hp, (hipStream_t)stream);
 }
 strait_status strait_k_global_avgpool(void* stream, const void* x, int32_t N, int32_t HW, int32_t C, void* y, int32_t hp) {
     return launch_global_avgpool((const half_t*)x, N, HW, C, (half_t*)y, hp, (hipStream_t)stream);

@@ -322,6 +322,78 @@ int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, 
 }
 
 // ------------------------------------------------------------------------------------------
+// max pooling 2x2 / stride 2, no padding (H, W even).  Thread = 8 channels of one output pixel.
+__global__ void __launch_bounds__(256) maxpool2x2s2_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
+                                                            half_t* __restrict__ y, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int C8 = C >> 3, P = H >> 1, Q = W >> 1;
+    const long long total = (long long)N * P * Q * C8;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c8 = (int)(i % C8);
+    long long t = i / C8;
+    const int q = (int)(t % Q); t /= Q;
+    const int pp = (int)(t % P);
+    const int n = (int)(t / P);
+    const half_t* src = x + (((long long)n * H + 2 * pp) * W + 2 * q) * C + c8 * 8;
+    const half8 a = *(const half8*)src, b = *(const half8*)(src + C);
+    const half8 c = *(const half8*)(src + (long long)W * C), d = *(const half8*)(src + (long long)W * C + C);
+    const half8 m = __builtin_elementwise_max(__builtin_elementwise_max(a, b), __builtin_elementwise_max(c, d));
+    *(half8*)(y + (((long long)n * P + pp) * Q + q) * C + c8 * 8) = m;
+}
+
+int launch_maxpool2x2s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream) {
+    if (!x || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || H % 2 != 0 || W % 2 != 0) {
+        set_error("maxpool 2x2: needs C %% 8 == 0 and even H, W"); return -5;
+    }
+    const long long blocks = ((long long)N * (H / 2) * (W / 2) * (C / 8) + 255) / 256;
+    if (blocks > 0x7fffffffLL) { set_error("maxpool 2x2: grid too large"); return -5; }
+    hipLaunchKernelGGL(maxpool2x2s2_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, y, hp);
+    STRAIT_CHECK_LAUNCH("maxpool 2x2");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Token assembly of a Vision Transformer: z[n][0] = cls + pos[0], z[n][1 + t] = patch[n][t] + pos[1 + t],
+// sums in fp32 rounded once.  patch [N][T][D], cls [D], pos [T + 1][D] fp32, z [N][T + 1][D].
+__global__ void __launch_bounds__(256) vit_tokens_kernel(const half_t* __restrict__ patch, const float* __restrict__ cls,
+                                                          const float* __restrict__ pos, int N, int T, int D,
+                                                          half_t* __restrict__ z, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const int D8 = D >> 3;
+    const long long total = (long long)N * (T + 1) * D8;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int d8 = (int)(i % D8);
+    long long t = i / D8;
+    const int tok = (int)(t % (T + 1));
+    const int n = (int)(t / (T + 1));
+    float v[8];
+    if (tok == 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = cls[d8 * 8 + j];
+    } else {
+        const half8 h = *(const half8*)(patch + ((long long)n * T + tok - 1) * D + d8 * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (float)h[j];
+    }
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (half_t)(v[j] + pos[(long long)tok * D + d8 * 8 + j]);
+    *(half8*)(z + ((long long)n * (T + 1) + tok) * D + d8 * 8) = o;
+}
+
+int launch_vit_tokens(const half_t* patch, const float* cls, const float* pos, int N, int T, int D, half_t* z, int hp,
+                      hipStream_t stream) {
+    if (!patch || !cls || !pos || !z || N <= 0 || T <= 0 || D <= 0 || D % 8 != 0) { set_error("tokens: needs D %% 8 == 0"); return -5; }
+    const long long blocks = ((long long)N * (T + 1) * (D / 8) + 255) / 256;
+    if (blocks > 0x7fffffffLL) { set_error("tokens: grid too large"); return -5; }
+    hipLaunchKernelGGL(vit_tokens_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, patch, cls, pos, N, T, D, z, hp);
+    STRAIT_CHECK_LAUNCH("tokens");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
 // global average pooling: [N][HW][C] -> [N][C], fp32 sum / HW, rounded once to fp16.
 // A workgroup covers 32 channel groups (256 channels) of one image; its 8 wavefront-halves each
 // sum every 8th position and the partial sums meet in LDS, so the loads of one image are spread
@@ -479,13 +551,13 @@ int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, in
 template <int MAXC>
 __global__ void __launch_bounds__(256) layernorm_kernel(const half_t* __restrict__ x, const float* __restrict__ gamma,
                                                          const float* __restrict__ beta, int rows, int n, float eps,
-                                                         half_t* __restrict__ y, int hp) {
+                                                         half_t* __restrict__ y, int hp, long long x_row_stride) {
     if (hp) __builtin_amdgcn_s_setprio(3);
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const int nch = n >> 3;
-    const half_t* src = x + (long long)row * n;
+    const half_t* src = x + (long long)row * x_row_stride;
     float v[MAXC][8];
     float s = 0.f;
 #pragma unroll
@@ -521,18 +593,19 @@ __global__ void __launch_bounds__(256) layernorm_kernel(const half_t* __restrict
 }
 
 int launch_layernorm(const half_t* x, const float* gamma, const float* beta, int rows, int n, float eps,
-                     half_t* y, int hp, hipStream_t stream) {
-    if (!x || !gamma || !beta || !y || rows <= 0 || n <= 0 || n % 8 != 0 || n > 8192) {
-        set_error("layernorm: needs n %% 8 == 0 and n <= 8192"); return -5;
+                     half_t* y, int hp, hipStream_t stream, long long x_row_stride) {
+    if (x_row_stride == 0) x_row_stride = n;
+    if (!x || !gamma || !beta || !y || rows <= 0 || n <= 0 || n % 8 != 0 || n > 8192 || x_row_stride < n || x_row_stride % 8 != 0) {
+        set_error("layernorm: needs n %% 8 == 0, n <= 8192 and a row stride that is a multiple of 8, at least n"); return -5;
     }
     const dim3 grid((rows + 3) / 4), block(256);
     const int nch = n / 8;
     if (nch <= 128)
-        hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+        hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     else if (nch <= 512)
-        hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+        hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     else
-        hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp);
+        hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     STRAIT_CHECK_LAUNCH("layernorm");
     return 0;
 }

@@ -50,11 +50,15 @@ int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, in
 int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
                      int stride, int act, half_t* y, int hp, hipStream_t stream);
 int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream);
+int launch_maxpool2x2s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream);
+int launch_vit_tokens(const half_t* patch, const float* cls, const float* pos, int N, int T, int D, half_t* z, int hp,
+                      hipStream_t stream);
 int launch_global_avgpool(const half_t* x, int N, int HW, int C, half_t* y, int hp, hipStream_t stream);
 int launch_softmax_top1(const float* logits, int rows, int n, float* probs, int32_t* top1, int hp,
                         hipStream_t stream);
+// x_row_stride: elements between consecutive input rows (0 = n); the output rows are contiguous.
 int launch_layernorm(const half_t* x, const float* gamma, const float* beta, int rows, int n, float eps,
-                     half_t* y, int hp, hipStream_t stream);
+                     half_t* y, int hp, hipStream_t stream, long long x_row_stride = 0);
 int launch_attention(const half_t* qkv, const int32_t* valid_len, int B, int S, int heads, half_t* out, int hp,
                      hipStream_t stream);
 int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, int32_t* top1, int hp,

@@ -345,6 +345,7 @@ struct Builder {
         op.in = in; op.out = out; op.out_ref = out_ref;
         op.H = H; op.W = W; op.C = C; op.K = C;
         if (sub == POOL_MAX3X3S2) { op.P = osz(H, 3, 2, 1); op.Q = osz(W, 3, 2, 1); }
+        if (sub == POOL_MAX2X2S2) { op.P = H / 2; op.Q = W / 2; }
         op.info.bytes_per_sample = 2LL * ((int64_t)H * W * C + (int64_t)op.P * op.Q * C);
         m.ops.push_back(op);
     }
@@ -354,6 +355,30 @@ struct Builder {
         const int f = pl.get(C);
         pool("gap", POOL_GLOBAL_AVG, feat_in, HW_h, HW_w, C, f);
         pl.put(feat_in);
+        return head(f, C, classes);
+    }
+
+    // a plain linear layer on one feature vector per sample: y = act(x W^T + b), fp16
+    int dense(const std::string& name, int in, int C, int K, int act, int out) {
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = in; op.out = out; op.act = act;
+        op.C = C; op.K = K; op.vC = C; op.vR = op.vS = 1; op.vH = op.vW = 1;
+        op.sN = C; op.sH = C; op.sW = C;
+        unsigned nout = 0;
+        int rc = ld.linear_weights({name}, C, op, &nout);
+        if (rc) return rc;
+        if ((int)nout != K) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), K, nout); return STRAIT_E_FORMAT; }
+        op.info.macs_per_sample = (int64_t)C * K;
+        op.info.bytes_per_sample = 2LL * C + 2LL * K;
+        op.info.gemm_m_per_sample = 1; op.info.gemm_n = K; op.info.gemm_k = C;
+        m.ops.push_back(op);
+        return 0;
+    }
+
+    // FC on a feature vector f [C] (fp32 logits into the output buffer) -> softmax + top-1
+    int head(int f, int C, int classes) {
         Op fc;
         name_op(fc, "fc", 0);
         fc.kind = OP_CONV;
@@ -476,6 +501,171 @@ static int plan_mobilenet_v2(Model& m, Builder& b) {
     return b.classifier(hd, P, Q, 1280, classes);
 }
 
+// VGG-19: 3x3 convolutions with bias and ReLU, 2x2 max pooling after the 2nd, 4th, 8th, 12th and 16th, then three
+// fully connected layers.  The first of them reads the last feature map flattened channel-major in the
+// container; its weight [out, C, h, w] is re-laid like a convolution's to [out][h][w][C], which is the order the
+// NHWC feature map already has in memory, so the layer is a plain matrix product over h*w*C inputs.
+static int plan_vgg19(Model& m, Builder& b) {
+    const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3], fcw = m.hyper[4];
+    if (H % 32 != 0 || W % 32 != 0 || fcw <= 0 || fcw % 8 != 0) { set_error("VGG-19: H and W must be multiples of 32 and the FC width a multiple of 8"); return STRAIT_E_SHAPE; }
+    static const int cfg[21] = {64, 64, 0, 128, 128, 0, 256, 256, 256, 256, 0, 512, 512, 512, 512, 0, 512, 512, 512, 512, 0};
+    int cur = SLOT_NONE, P = H, Q = W, cin = C, idx = 0, rc;
+    for (int i = 0; i < 21; ++i) {
+        char nm[16];
+        if (cfg[i] == 0) {
+            const int o = b.pl.get((size_t)(P / 2) * (Q / 2) * cin);
+            snprintf(nm, sizeof(nm), "pool%d", idx);
+            b.pool(nm, POOL_MAX2X2S2, cur, P, Q, cin, o);
+            b.pl.put(cur);
+            cur = o; P /= 2; Q /= 2;
+            continue;
+        }
+        snprintf(nm, sizeof(nm), "conv%d", idx);
+        if (idx == 0) {
+            if ((rc = b.stem(nm, false, H, W, C, cfg[i], 3, 1, 1, ACT_RELU, 0, &cur, &P, &Q))) return rc;
+        } else {
+            const int o = b.pl.get((size_t)P * Q * cfg[i]);
+            if ((rc = b.conv(nm, false, cur, P, Q, cin, cfg[i], 3, 1, 1, ACT_RELU, SLOT_NONE, o, nullptr, nullptr))) return rc;
+            b.pl.put(cur);
+            cur = o;
+        }
+        cin = cfg[i];
+        ++idx;
+    }
+    // fc1: a P x Q "convolution" without padding on the P x Q feature map = one output position
+    const int f1 = b.pl.get(fcw);
+    {
+        Op op;
+        name_op(op, "fc1", 0);
+        op.kind = OP_CONV;
+        op.in = cur; op.out = f1; op.act = ACT_RELU;
+        const int Cin = P * Q * cin;
+        op.C = Cin; op.K = fcw; op.vC = Cin; op.vR = op.vS = 1; op.vH = op.vW = 1;
+        op.sN = Cin; op.sH = Cin; op.sW = Cin;
+        if ((rc = b.ld.conv_weights("fc1", false, fcw, cin, P, Q, op))) return rc;
+        op.info.macs_per_sample = (int64_t)Cin * fcw;
+        op.info.bytes_per_sample = 2LL * Cin + 2LL * fcw;
+        op.info.gemm_m_per_sample = 1; op.info.gemm_n = fcw; op.info.gemm_k = Cin;
+        m.ops.push_back(op);
+    }
+    b.pl.put(cur);
+    const int f2 = b.pl.get(fcw);
+    if ((rc = b.dense("fc2", f1, fcw, fcw, ACT_RELU, f2))) return rc;
+    b.pl.put(f1);
+    rc = b.head(f2, fcw, classes);
+    return rc;
+}
+
+// Vision Transformer with 16x16 patches, pre-LayerNorm blocks:
+//   tokens = [cls ; patches W_p + b_p] + pos;  z += Attn(LN1(z)) W_o + b_o;  z += GELU(LN2(z) W_1 + b_1) W_2 + b_2;
+//   logits = LN(z)[token 0] W_h + b_h.
+// The patch embedding is a 16x16 convolution of stride 16 (the stem path: its row taps are contiguous in memory);
+// every sequence has the same length, so the attention kernel's valid lengths are all S.
+static int plan_vit(Model& m, Builder& b) {
+    const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3];
+    const int layers = m.hyper[4], hidden = m.hyper[5], heads = m.hyper[6], ffn = m.hyper[7];
+    if (H % 16 != 0 || W % 16 != 0) { set_error("ViT: H and W must be multiples of the 16-pixel patch"); return STRAIT_E_SHAPE; }
+    if (layers <= 0 || heads <= 0 || hidden != heads * 64) { set_error("ViT: head dimension must be 64 (hidden %d, heads %d)", hidden, heads); return STRAIT_E_SHAPE; }
+    if (ffn <= 0 || ffn % 8 != 0) { set_error("ViT: ffn width must be a multiple of 8"); return STRAIT_E_SHAPE; }
+    const int T = (H / 16) * (W / 16), seq = T + 1;
+    if (seq > 256) { set_error("ViT: %d tokens, at most 256 are supported", seq); return STRAIT_E_SHAPE; }
+    m.seq = seq; m.hidden = hidden;
+    Loader& ld = b.ld;
+    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) -> int {
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = in; op.out = out; op.res = res; op.act = act;
+        op.P = seq; op.Q = 1; op.H = seq; op.W = 1;
+        op.C = K; op.K = N; op.vC = K; op.vR = op.vS = 1; op.vH = op.vW = 1;
+        op.sN = K; op.sH = K; op.sW = K;
+        unsigned nout = 0;
+        int rc = ld.linear_weights(ws, K, op, &nout);
+        if (rc) return rc;
+        if ((int)nout != N) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), N, nout); return STRAIT_E_FORMAT; }
+        op.info.macs_per_sample = (int64_t)seq * K * N;
+        op.info.bytes_per_sample = 2LL * seq * ((int64_t)K + (int64_t)N * (res != SLOT_NONE ? 2 : 1));
+        op.info.gemm_m_per_sample = seq; op.info.gemm_n = N; op.info.gemm_k = K;
+        m.ops.push_back(op);
+        return 0;
+    };
+    auto lnorm = [&](const std::string& name, int in, int out, int rows, long long in_stride) -> int {
+        Op op;
+        name_op(op, name, 4);
+        op.kind = OP_LAYERNORM;
+        op.in = in; op.out = out; op.P = rows; op.K = hidden; op.eps = 1e-6f; op.in_row_stride = in_stride;
+        int rc;
+        if ((rc = ld.vector_f32(name + ".g", hidden, &op.bias))) return rc;
+        if ((rc = ld.vector_f32(name + ".b", hidden, &op.beta))) return rc;
+        op.info.bytes_per_sample = 4LL * rows * hidden;
+        op.info.weight_bytes = 8LL * hidden;
+        m.ops.push_back(op);
+        return 0;
+    };
+    int patches, P, Q, rc;
+    if ((rc = b.stem("patch", false, H, W, C, hidden, 16, 16, 0, ACT_NONE, 0, &patches, &P, &Q))) return rc;
+    const size_t tok = (size_t)seq * hidden;
+    int z = b.pl.get(tok);
+    {
+        Op op;
+        name_op(op, "tokens", 6);
+        op.kind = OP_TOKENS;
+        op.in = patches; op.out = z; op.P = seq; op.K = hidden;     // P: rows written per sample (T patches + the class token)
+        if ((rc = ld.vector_f32("cls", hidden, &op.bias))) return rc;
+        const TensorView* pos = ld.c.find("pos");
+        if (!pos || pos->ndim != 2 || pos->shape[0] != (unsigned)seq || pos->shape[1] != (unsigned)hidden) { set_error("'pos': expected [%d,%d]", seq, hidden); return STRAIT_E_FORMAT; }
+        std::vector<float> f(pos->count);
+        for (size_t i = 0; i < pos->count; ++i) f[i] = (float)pos->data[i];
+        void* d = nullptr;
+        if ((rc = ld.upload(f.data(), f.size() * 4, &d))) return rc;
+        op.beta = (const float*)d;
+        op.info.bytes_per_sample = 2LL * ((int64_t)T * hidden + (int64_t)seq * hidden);
+        op.info.weight_bytes = 4LL * (seq + 1) * hidden;
+        m.ops.push_back(op);
+    }
+    b.pl.put(patches);
+    for (int i = 0; i < layers; ++i) {
+        char pre[16];
+        snprintf(pre, sizeof(pre), "l%d", i);
+        const std::string p(pre);
+        const int n1 = b.pl.get(tok);
+        if ((rc = lnorm(p + ".ln1", z, n1, seq, 0))) return rc;
+        const int qkv = b.pl.get(3 * tok);
+        if ((rc = gemm(p + ".qkv", {p + ".q", p + ".k", p + ".v"}, n1, hidden, 3 * hidden, ACT_NONE, SLOT_NONE, qkv))) return rc;
+        b.pl.put(n1);
+        const int att = b.pl.get(tok);
+        {
+            Op op;
+            name_op(op, p + ".attn", 5);
+            op.kind = OP_ATTENTION;
+            op.in = qkv; op.out = att; op.seq = seq; op.heads = heads; op.P = seq; op.K = hidden;
+            op.info.macs_per_sample = 2LL * seq * seq * hidden;
+            op.info.bytes_per_sample = 2LL * seq * hidden * 4;
+            m.ops.push_back(op);
+        }
+        b.pl.put(qkv);
+        const int z1 = b.pl.get(tok);
+        if ((rc = gemm(p + ".o", {p + ".o"}, att, hidden, hidden, ACT_NONE, z, z1))) return rc;
+        b.pl.put(att);
+        b.pl.put(z);
+        const int n2 = b.pl.get(tok);
+        if ((rc = lnorm(p + ".ln2", z1, n2, seq, 0))) return rc;
+        const int f = b.pl.get((size_t)seq * ffn);
+        if ((rc = gemm(p + ".ffn1", {p + ".ffn1"}, n2, hidden, ffn, ACT_GELU, SLOT_NONE, f))) return rc;
+        b.pl.put(n2);
+        const int z2 = b.pl.get(tok);
+        if ((rc = gemm(p + ".ffn2", {p + ".ffn2"}, f, ffn, hidden, ACT_NONE, z1, z2))) return rc;
+        b.pl.put(f);
+        b.pl.put(z1);
+        z = z2;
+    }
+    // the head reads token 0 only: the closing LayerNorm runs on that row of every sample
+    const int feat = b.pl.get(hidden);
+    if ((rc = lnorm("ln", z, feat, 1, (long long)seq * hidden))) return rc;
+    b.pl.put(z);
+    return b.head(feat, hidden, classes);
+}
+
 static int plan_encoder(Model& m, Builder& b) {
     const int layers = m.hyper[0], hidden = m.hyper[1], heads = m.hyper[2], ffn = m.hyper[3], seq = m.hyper[4];
     if (heads <= 0 || hidden != heads * 64) { set_error("encoder: head dimension must be 64 (hidden %d, heads %d)", hidden, heads); return STRAIT_E_SHAPE; }
@@ -593,6 +783,16 @@ int build_plan(Model& m, const void* blob, size_t bytes) {
             m.classes = m.hyper[3];
             rc = m.arch == STRAIT_ARCH_TINY_CNN ? plan_tiny_cnn(m, b) : m.arch == STRAIT_ARCH_RESNET50 ? plan_resnet50(m, b) : plan_mobilenet_v2(m, b);
             break;
+        case STRAIT_ARCH_VGG19:
+        case STRAIT_ARCH_VIT:
+            if (m.hyper[0] <= 0 || m.hyper[1] <= 0 || m.hyper[2] != 3 || m.hyper[3] <= 0 || m.hyper[0] > 4096 || m.hyper[1] > 4096) {
+                set_error("image model hyper-parameters out of range (H %d, W %d, C %d, classes %d)", m.hyper[0], m.hyper[1], m.hyper[2], m.hyper[3]);
+                return STRAIT_E_SHAPE;
+            }
+            m.in_elems = (size_t)m.hyper[0] * m.hyper[1] * m.hyper[2];
+            m.classes = m.hyper[3];
+            rc = m.arch == STRAIT_ARCH_VGG19 ? plan_vgg19(m, b) : plan_vit(m, b);
+            break;
         case STRAIT_ARCH_ENCODER:
             if (m.hyper[0] <= 0 || m.hyper[1] <= 0 || m.hyper[3] <= 0) { set_error("encoder hyper-parameters out of range"); return STRAIT_E_SHAPE; }
             m.seq = m.hyper[4]; m.hidden = m.hyper[1];
@@ -666,6 +866,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 break;
             case OP_POOL:
                 if (op.sub == POOL_MAX3X3S2) rc = launch_maxpool3x3s2((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, hp, stream);
+                else if (op.sub == POOL_MAX2X2S2) rc = launch_maxpool2x2s2((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, hp, stream);
                 else if (op.sub == POOL_GLOBAL_AVG) rc = launch_global_avgpool((const half_t*)src, batch, op.H * op.W, op.C, (half_t*)dst, hp, stream);
                 else rc = launch_argmax_f16((const half_t*)src, batch, op.K, (long long)op.P * op.K, (int32_t*)dst, hp, stream);
                 break;
@@ -673,7 +874,10 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 rc = launch_softmax_top1((const float*)src, batch, op.K, (float*)dst, (int32_t*)slot_ptr(m, in, SLOT_OUT, op.out_ref2, batch), hp, stream);
                 break;
             case OP_LAYERNORM:
-                rc = launch_layernorm((const half_t*)src, op.bias, op.beta, batch * op.P, op.K, op.eps, (half_t*)dst, hp, stream);
+                rc = launch_layernorm((const half_t*)src, op.bias, op.beta, batch * op.P, op.K, op.eps, (half_t*)dst, hp, stream, op.in_row_stride);
+                break;
+            case OP_TOKENS:
+                rc = launch_vit_tokens((const half_t*)src, op.bias, op.beta, batch, op.P - 1, op.K, (half_t*)dst, hp, stream);
                 break;
             case OP_ATTENTION:
                 rc = launch_attention((const half_t*)src, in.dev_valid, batch, op.seq, op.heads, (half_t*)dst, hp, stream);

@@ -18,8 +18,8 @@
 
 namespace strait {
 
-enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_POOL = 2, OP_SOFTMAX = 3, OP_LAYERNORM = 4, OP_ATTENTION = 5, OP_PACK = 6 };
-enum PoolKind { POOL_MAX3X3S2 = 0, POOL_GLOBAL_AVG = 1, POOL_ARGMAX = 2 };
+enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_POOL = 2, OP_SOFTMAX = 3, OP_LAYERNORM = 4, OP_ATTENTION = 5, OP_PACK = 6, OP_TOKENS = 7 };
+enum PoolKind { POOL_MAX3X3S2 = 0, POOL_GLOBAL_AVG = 1, POOL_ARGMAX = 2, POOL_MAX2X2S2 = 3 };
 
 // Where an operand lives.  Slots >= 0 index the instance's activation buffers; the input and
 // output slots are the instance's device input / output buffers (output at a byte offset that
@@ -50,9 +50,10 @@ struct Op {
     // attention / layernorm
     int seq = 0, heads = 0;
     float eps = 0.f;
+    long long in_row_stride = 0;      // LayerNorm: elements between input rows (0 = contiguous)
     const half_t* w = nullptr;
-    const float* bias = nullptr;      // conv/gemm bias, LayerNorm gamma
-    const float* beta = nullptr;      // LayerNorm beta
+    const float* bias = nullptr;      // conv/gemm bias, LayerNorm gamma, class token (OP_TOKENS)
+    const float* beta = nullptr;      // LayerNorm beta, position embeddings (OP_TOKENS)
     strait_layer_info info{};
 };
 

@@ -148,7 +148,10 @@ def test_layernorm(S, rows, n):
 
 
 @pytest.mark.parametrize("B,Sq,heads,lens", [(3, 128, 12, (128, 32, 77)), (2, 64, 2, (64, 5)), (4, 32, 1, (1, 16, 31, 32)),
-                                             (2, 128, 4, (33, 100))])
+                                             (2, 128, 4, (33, 100)),
+                                             # lengths that are no multiple of the 32-row blocks, and more than 128 keys
+                                             (3, 197, 12, (197, 197, 150)), (2, 37, 2, (37, 20)), (3, 17, 1, (17, 1, 16)),
+                                             (2, 256, 2, (256, 129)), (2, 129, 3, (129, 128)), (2, 255, 1, (255, 97))])
 def test_attention(S, B, Sq, heads, lens):
     hid = heads * 64
     qkv = f16(R.standard_normal((B, Sq, 3 * hid)))
@@ -166,6 +169,23 @@ def test_attention(S, B, Sq, heads, lens):
     out2 = S.k_attention(dev(S, qkv2), dev(S, vl), heads).float().cpu().numpy()
     for b in range(B):
         assert np.array_equal(out2[b, :vl[b]], out[b, :vl[b]])
+
+
+@pytest.mark.parametrize("n,h,w,c", [(2, 8, 6, 16), (3, 14, 14, 512), (1, 224, 224, 64)])
+def test_maxpool2x2(S, n, h, w, c):
+    x = f16(R.standard_normal((n, h, w, c)))
+    y = S.k_maxpool2x2s2(dev(S, x)).float().cpu().numpy()
+    assert np.array_equal(y, ops.maxpool2d(x, 2, 2, 0))          # selection only: bit-exact
+
+
+@pytest.mark.parametrize("n,t,d", [(2, 9, 64), (3, 196, 768)])
+def test_vit_tokens(S, n, t, d):
+    patch = f16(R.standard_normal((n, t, d)))
+    cls = f16(R.standard_normal(d) * 0.02).astype(np.float32)
+    pos = f16(R.standard_normal((t + 1, d)) * 0.02).astype(np.float32)
+    z = S.k_vit_tokens(dev(S, patch), dev(S, cls), dev(S, pos)).float().cpu().numpy()
+    ref = np.concatenate([np.broadcast_to(cls.astype(np.float64), (n, 1, d)), patch.astype(np.float64)], axis=1) + pos.astype(np.float64)
+    check_kernel(z, ref, "vit tokens", rel=2.0 ** -10, abs_rel=1e-3)
 
 
 def test_argmax_f16(S):

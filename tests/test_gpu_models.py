@@ -114,6 +114,67 @@ def test_encoder(ctx, kw, batch):
     m.free()
 
 
+@pytest.mark.parametrize("hw,batch,fc", [(32, 5, 64), (64, 3, 256)])
+def test_vgg19(ctx, hw, batch, fc):
+    md = synth.vgg19(synth.SEEDS[synth.ARCH_VGG19], hw=hw, classes=100, fc=fc)
+    x = synth.default_image_batch(md, batch, synth.SEEDS[synth.ARCH_VGG19] + batch)
+    m, out, ref = run_cnn(ctx, md, x, omodels.vgg19_forward, ctx.S.PRIO_LOW, f"VGG-19 {hw}px b{batch}")
+    m.free()
+
+
+def test_vgg19_layers(ctx):
+    """Every layer's activation against the oracle's: pooling positions, the flattening order into fc1."""
+    md = synth.vgg19(4, hw=64, classes=10, fc=64)
+    x = synth.default_image_batch(md, 2, 9)
+    m = ctx.load(synth.pack(md), max_batch=2, n_instances=1)
+    ref = omodels.vgg19_forward(md.tensors, x, keep=True)
+    m.copy_in(0, ctx.S.PRIO_LOW, x)
+    m.run(0, ctx.S.PRIO_LOW, 2)
+    m.sync(0, ctx.S.PRIO_LOW)
+    names = {li.name.decode(): i for i, li in enumerate(m.layers())}
+    checked = 0
+    for lname, act in ref.trace.acts.items():
+        if lname not in names or lname == "fc":
+            continue
+        got = m.read_activation(0, names[lname], 2).astype(np.float64).reshape(act.shape)
+        check_kernel(got, act, f"layer {lname}", rel=2.0 ** -8, abs_rel=1e-2)
+        checked += 1
+    assert checked == 16 + 5 + 2
+    m.free()
+
+
+def run_vit(ctx, md, x, what):
+    m = ctx.load(synth.pack(md), max_batch=x.shape[0], n_instances=1)
+    out, rec = m.infer(x, prio=ctx.S.PRIO_HIGH)
+    ref = omodels.vit_forward(md.tensors, x, md.hyper, keep=True)
+    err, scale, ties = check_logits(out["logits"], ref.logits, out["top1"], what)
+    assert np.abs(out["probs"] - ref.probs).max() <= 2e-2
+    print(f"{what}: max|err| {err:.3e} of scale {scale:.3e} ({err / scale:.2e}), ties {ties}, kernels {rec.kernel_ms:.3f} ms")
+    return m, out, ref
+
+
+@pytest.mark.parametrize("hw,batch,kw", [(48, 3, dict(layers=2, hidden=128, heads=2, ffn=256)),     # 10 tokens
+                                         (96, 2, dict(layers=2, hidden=128, heads=2, ffn=256)),     # 37 tokens
+                                         (224, 2, dict(layers=2, hidden=192, heads=3, ffn=384))])   # 197 tokens
+def test_vit(ctx, hw, batch, kw):
+    md = synth.vit(synth.SEEDS[synth.ARCH_VIT], hw=hw, classes=100, **kw)
+    x = synth.default_image_batch(md, batch, synth.SEEDS[synth.ARCH_VIT] + batch)
+    m, out, ref = run_vit(ctx, md, x, f"ViT {hw}px b{batch}")
+    # every block's output (the residual stream) against the oracle's
+    names = {li.name.decode(): i for i, li in enumerate(m.layers())}
+    m.copy_in(0, ctx.S.PRIO_LOW, x)
+    m.run(0, ctx.S.PRIO_LOW, batch)
+    m.sync(0, ctx.S.PRIO_LOW)
+    checked = 0
+    for lname in ("patch", "tokens", "l0.qkv", "l0.attn", "l0.o", "l0.ffn1", "l0.ffn2", "l1.o", "l1.ffn2", "ln"):
+        act = ref.trace.acts[lname]
+        got = m.read_activation(0, names[lname], batch).astype(np.float64).reshape(act.shape)
+        check_kernel(got, act, f"layer {lname}", rel=2.0 ** -8, abs_rel=1e-2)
+        checked += 1
+    assert checked == 10
+    m.free()
+
+
 def test_submit_errors_and_pool(ctx):
     S = ctx.S
     md = synth.tiny_cnn(1)
