@@ -79,3 +79,12 @@ def test_encoder_all_batches(ctx):
             print(f"encoder b{b}: max|err| {worst:.3e} = {worst / scale:.2e} of {scale:.2f}; ties {ties}")
     finally:
         m.free()
+
+
+def test_vgg19_full_size(ctx):
+    cnn_case(ctx, synth.ARCH_VGG19, omodels.vgg19_forward, (1, 6))
+
+
+def test_vit_b16_full_size(ctx):
+    md_hyper = (224, 224, 3, 1000, 12, 768, 12, 3072)                 # what synth.vit() draws by default
+    cnn_case(ctx, synth.ARCH_VIT, lambda t, x: omodels.vit_forward(t, x, md_hyper), (1, 8, 19))
