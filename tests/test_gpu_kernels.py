@@ -200,7 +200,7 @@ def test_launchers_reject_bad_shapes(S):
     with pytest.raises(S.StraitError):
         S.k_dwconv3x3(x, dev(S, np.zeros((3, 3, 12), np.float16)), None, 1)       # C % 8 != 0
     with pytest.raises(S.StraitError):
-        S.k_attention(dev(S, np.zeros((1, 48, 192), np.float16)), dev(S, np.array([48], np.int32)), 1)   # S % 32 != 0
+        S.k_attention(dev(S, np.zeros((1, 300, 192), np.float16)), dev(S, np.array([300], np.int32)), 1)   # more than 256 keys
     with pytest.raises(S.StraitError):
         S.k_layernorm(dev(S, np.zeros((2, 12), np.float16)), dev(S, np.ones(12, np.float32)), dev(S, np.zeros(12, np.float32)), 1e-5)
 
