@@ -139,6 +139,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-batch", action="store_true")
     ap.add_argument("--no-other-models", action="store_true", help="skip the VGG-19 and ViT-B/16 throughput lines")
+    ap.add_argument("--only-model", choices=("vgg19", "vit_b16"), default=None,
+                    help="time nothing but this model at batch 64 (for kernel profiles of the second workload set)")
     ap.add_argument("--colocation-seconds", type=float, default=5.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
     ap.add_argument("--serving-seconds", type=float, default=3.0,
@@ -185,6 +187,27 @@ def main() -> int:
         ev1.record(stream)
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ev0.elapsed_time(ev1)
+
+    def other_model(arch, steps=20, warmup=5):
+        omd = synth.make_model(arch, synth.SEEDS[arch])
+        om = ctx.load(synth.pack(omd), max_batch=64, n_instances=1)
+        om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
+        om.sync(0, prio)
+        odt, odev = timed(om, 64, steps, warmup)
+        macs = sum(l.macs_per_sample for l in om.layers())
+        res = {"batch": 64, "images_per_s": round(steps * 64 / odt, 1), "ms_per_step": round(odt / steps * 1e3, 4),
+               "tflops": round(2.0 * macs * 64 / (odev / steps * 1e-3) / 1e12, 1),
+               "frac_of_mfma_peak": round(2.0 * macs * 64 / (odev / steps * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+        om.free()
+        return res
+
+    others = {"vgg19": synth.ARCH_VGG19, "vit_b16": synth.ARCH_VIT}
+    if args.only_model:
+        # profiling aid: nothing but this model's steps is launched (no ResNet-50 step, no headline value)
+        print(json.dumps({"only_model": args.only_model, "steps": K, "warmup": W, **other_model(others[args.only_model], K, W)}))
+        model.free()
+        ctx.close()
+        return 0
 
     if args.copy_calibration_mb > 0:
         src = torch.empty(args.copy_calibration_mb << 20, dtype=torch.uint8, device="cuda").zero_()
@@ -305,20 +328,7 @@ def main() -> int:
     if not args.no_other_models:
         # the paper's other image classifiers by shape (Table 1): VGG-19 (all 3x3 convolutions, MFMA-bound) and
         # ViT-B/16 (197 tokens), batch 64, input resident, same timing as the headline value
-        others = {}
-        for arch, name in ((synth.ARCH_VGG19, "vgg19"), (synth.ARCH_VIT, "vit_b16")):
-            omd = synth.make_model(arch, synth.SEEDS[arch])
-            om = ctx.load(synth.pack(omd), max_batch=64, n_instances=1)
-            om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
-            om.sync(0, prio)
-            odt, odev = timed(om, 64, 20, 5)
-            macs = sum(l.macs_per_sample for l in om.layers())
-            others[name] = {"batch": 64, "images_per_s": round(20 * 64 / odt, 1), "ms_per_step": round(odt / 20 * 1e3, 4),
-                            "tflops": round(2.0 * macs * 64 / (odev / 20 * 1e-3) / 1e12, 1),
-                            "frac_of_mfma_peak": round(2.0 * macs * 64 / (odev / 20 * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
-            om.free()
-            del omd
-        out["other_models"] = others
+        out["other_models"] = {name: other_model(arch) for name, arch in others.items()}
 
     if args.colocation_seconds > 0:
         out["colocation"] = colocation(ctx, md, blob, args.colocation_seconds)
