@@ -427,6 +427,8 @@ typedef struct strait_server_stats {
 strait_status strait_server_create(strait_sched* sched, int32_t concurrency, int64_t retry_ns,
                                    const strait_executor* executor, strait_server** out);
 strait_status strait_server_add_model(strait_server* s, const strait_server_model* desc);   /* before start */
+/* With the library's own executor, start first runs every (instance, batch size) of every model twice and one
+ * burst of `concurrency` batches, so that no request pays for a first use (graph capture, runtime pools). */
 strait_status strait_server_start(strait_server* s);
 /* Non-blocking, thread-safe.  host_in (one sample, the model's input layout) and host_out (one sample's
  * output, the layout of strait_model_io at batch 1) must stay valid until the request's record has been

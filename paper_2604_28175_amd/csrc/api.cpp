@@ -198,6 +198,7 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
     for (Instance& in : m->inst) {
         bool ok = hipHostMalloc(&in.pinned_in, inb + (size_t)d->max_batch * 4, hipHostMallocDefault) == hipSuccess &&
                   hipHostMalloc(&in.pinned_out, outb, hipHostMallocDefault) == hipSuccess &&
+                  hipHostGetDevicePointer(&in.pinned_out_dev, in.pinned_out, 0) == hipSuccess &&
                   hipMalloc(&in.dev_in, inb) == hipSuccess && hipMalloc(&in.dev_out, outb) == hipSuccess &&
                   hipMalloc((void**)&in.dev_valid, (size_t)d->max_batch * 4 + 256) == hipSuccess &&
                   hipMalloc((void**)&in.splitk_ws, SPLITK_WS_BYTES) == hipSuccess;
@@ -223,6 +224,9 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
             free_model(m);
             return STRAIT_E_NOMEM;
         }
+        // The runtime sets a stream's hardware queue up at the first launch on it, which takes milliseconds:
+        // do that here and not under the first batch that happens to use this instance's side stream.
+        if (launch_fill_zero(in.splitk_ws, 256, in.side) != 0) { free_model(m); return STRAIT_E_HIP; }
         // valid lengths default to the full sequence
         if (m->arch == STRAIT_ARCH_ENCODER || m->arch == STRAIT_ARCH_VIT) {
             std::vector<int32_t> full(d->max_batch, m->seq);
@@ -376,7 +380,7 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
         if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
         if (!rc) rc = run_batch(*m, in, batch, s, hp_flag(c, prio));
         if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-        if (!rc) rc = hipMemcpyAsync(in.pinned_out, in.dev_out, m->out_bytes(batch), hipMemcpyDeviceToHost, s) == hipSuccess ? 0 : STRAIT_E_HIP;
+        if (!rc) rc = launch_copy_out(in.dev_out, in.pinned_out_dev, m->out_bytes(batch), hp_flag(c, prio), s);
         if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
         if (!rc) {
             t->rec.t_issued_ns = now_ns();

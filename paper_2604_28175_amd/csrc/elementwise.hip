@@ -6,6 +6,8 @@
 // writes its result once, so the design rule is 16-byte accesses that are contiguous across
 // the lanes of a wavefront (the channel axis of NHWC), fp32 arithmetic in registers, and
 // enough workgroups (>> 256) to cover the chip.
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace strait {
@@ -39,6 +41,31 @@ int launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
     unsigned blocks = (unsigned)((n16 + 255) / 256 > 4096 ? 4096 : (n16 + 255) / 256);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, (uint4*)p, n16);
     STRAIT_CHECK_LAUNCH("fill");
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Result hand-over: device buffer -> pinned host memory that the GPU can address, written by a kernel.
+// (A device-to-host hipMemcpyAsync of these few kilobytes sometimes blocks the submitting thread for
+// milliseconds when other streams are busy; a kernel launch does not.)  Both pointers 16-byte aligned,
+// bytes a multiple of 4.
+__global__ void __launch_bounds__(256) copy_out_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, size_t n4, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const size_t n16 = n4 >> 2;
+    const size_t step = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += step) ((uint4*)dst)[i] = ((const uint4*)src)[i];
+    const size_t tail = n16 << 2;
+    if (blockIdx.x == 0 && tail + threadIdx.x < n4) dst[tail + threadIdx.x] = src[tail + threadIdx.x];
+}
+int launch_copy_out(const void* src, void* dst_host_mapped, size_t bytes, int hp, hipStream_t stream) {
+    if (bytes == 0) return 0;
+    if (!src || !dst_host_mapped || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst_host_mapped) & 15) || (bytes & 3)) {
+        set_error("copy out: 16-byte aligned buffers and a multiple of 4 bytes required"); return -1;
+    }
+    const size_t n4 = bytes / 4, n16 = n4 / 4;
+    const unsigned blocks = (unsigned)std::min<size_t>(256, std::max<size_t>(1, (n16 + 255) / 256));
+    hipLaunchKernelGGL(copy_out_kernel, dim3(blocks), dim3(256), 0, stream, (const uint32_t*)src, (uint32_t*)dst_host_mapped, n4, hp);
+    STRAIT_CHECK_LAUNCH("copy out");
     return 0;
 }
 

@@ -60,6 +60,7 @@ struct Op {
 struct Instance {
     void* pinned_in = nullptr;
     void* pinned_out = nullptr;
+    void* pinned_out_dev = nullptr;    // the same memory as the GPU addresses it
     void* dev_in = nullptr;
     void* dev_out = nullptr;
     int32_t* dev_valid = nullptr;

@@ -382,6 +382,52 @@ strait_status strait_server_start(strait_server* s) {
     std::lock_guard<std::mutex> lk(s->mu);
     if (s->running || s->stopping) { set_error("server_start: already started"); return STRAIT_E_BUSY; }
     if (s->models.empty()) { set_error("server_start: no models"); return STRAIT_E_INVALID; }
+    if (!s->external) {
+        // Warm-up, so that no request pays for a first use: every (instance, batch size) runs twice (with graph
+        // replay switched on in the context, the second run captures that key's graph), then every instance of every model
+        // is submitted at once, three times over (the runtime grows its per-stream pools the first time streams are
+        // that deep, which stalls the submitting thread for milliseconds).
+        std::vector<strait_ticket> burst;
+        for (auto& kv : s->models) {
+            ModelQ& mq = kv.second;
+            std::vector<int32_t> valid(mq.d.max_batch, mq.seq);
+            for (int inst = 0; inst < mq.d.n_instances; ++inst) {
+                void* stage = nullptr;
+                size_t cap = 0;
+                int rc = strait_model_staging(mq.d.model, inst, &stage, &cap);
+                if (rc != STRAIT_OK) return rc;
+                memset(stage, 0, mq.in1 * (size_t)mq.d.max_batch);
+                for (int b = 1; b <= mq.d.max_batch; ++b)
+                    for (int rep = 0; rep < 2; ++rep) {
+                        strait_ticket tk = nullptr;
+                        rc = strait_submit(mq.d.model, (strait_priority)mq.d.priority, b, stage, valid.data(), mq.out_buf[inst].data(), &tk);
+                        if (rc == STRAIT_OK) rc = strait_wait(tk, nullptr);
+                        if (rc != STRAIT_OK) return rc;
+                    }
+            }
+        }
+        int rc = STRAIT_OK;
+        for (int round = 0; round < 3 && rc == STRAIT_OK; ++round) {
+            // every instance of every model at once, models interleaved: all streams as deep as they will ever be
+            burst.clear();
+            int max_inst = 0;
+            for (auto& kv : s->models) max_inst = std::max(max_inst, kv.second.d.n_instances);
+            for (int inst = 0; inst < max_inst && rc == STRAIT_OK; ++inst)
+                for (auto& kv : s->models) {
+                    ModelQ& mq = kv.second;
+                    if (inst >= mq.d.n_instances || rc != STRAIT_OK) continue;
+                    std::vector<int32_t> valid(mq.d.max_batch, mq.seq);
+                    void* stage = nullptr;
+                    size_t cap = 0;
+                    rc = strait_model_staging(mq.d.model, inst, &stage, &cap);
+                    strait_ticket tk = nullptr;
+                    if (rc == STRAIT_OK) rc = strait_submit(mq.d.model, (strait_priority)mq.d.priority, mq.d.max_batch, stage, valid.data(), mq.out_buf[inst].data(), &tk);
+                    if (rc == STRAIT_OK) burst.push_back(tk);
+                }
+            for (strait_ticket tk : burst) { const int r2 = strait_wait(tk, nullptr); if (rc == STRAIT_OK) rc = r2; }
+        }
+        if (rc != STRAIT_OK) return rc;
+    }
     s->running = true;
     s->sched_th = std::thread([s] { s->sched_loop(); });
     for (int i = 0; i < s->concurrency; ++i) s->exec_th.emplace_back([s] { s->exec_loop(); });
