@@ -87,7 +87,7 @@ def serving(ctx, md_resnet, blob_resnet, seconds, hp_rate, lp_rate):
     """The whole of the paper's system on one GPU: single requests for a high-priority ResNet-50 and a
     low-priority MobileNetV2 on Poisson schedules through the front end (maximum batch 8, four batches in
     flight, batch formation timeout a tenth of the deadline: Section 5.1), first the high-priority model
-    alone, then both."""
+    alone, then both, then both with twice the low-priority rate (more than its one stream can serve)."""
     import synth
     import paper_2604_28175_amd as strait
     from paper_2604_28175_amd import serve
@@ -110,14 +110,15 @@ def serving(ctx, md_resnet, blob_resnet, seconds, hp_rate, lp_rate):
                                  "b8": [round(p[7].t_inf_isol_ns * 1e-6, 3), round(p[7].t_kernel_isol_ns * 1e-6, 3)],
                                  "demand_b8": [round(v, 3) for v in p[7].m]} for name, p in (("hp", prof[1]), ("lp", prof[2]))}}
     ctx.set_graphs(True)      # a batch's kernel sequence is replayed from a captured graph: a fifth of the host time per submit
-    for phase, mids in (("hp_alone", (1,)), ("hp_and_lp", (1, 2))):
+    for phase, mids, lp_scale in (("hp_alone", (1,), 1.0), ("hp_and_lp", (1, 2), 1.0), ("hp_and_lp_overload", (1, 2), 2.0)):
         srv = strait.Server(sched, 4, 200_000)
         for mid in mids:
             c = cfg[mid]
             srv.add_model(c["model"], mid, c["prio"], 8, int(c["deadline_ms"] * 1e6), int(c["deadline_ms"] * 1e5))
         srv.start()
         streams = {mid: {"model": cfg[mid]["model"], "inputs": xs[mid],
-                         "arrivals_ns": synth.poisson_arrivals_ns(seed + mid, cfg[mid]["rate"], seconds)} for mid in mids}
+                         "arrivals_ns": synth.poisson_arrivals_ns(seed + mid, cfg[mid]["rate"] * (lp_scale if mid == 2 else 1.0), seconds)}
+                   for mid in mids}
         summ = serve.run_open_loop(srv, streams, seconds)
         st = srv.stats()
         srv.close()
