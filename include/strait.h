@@ -205,6 +205,13 @@ strait_status strait_k_gemm(void* stream, const void* x, const void* w, const fl
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,
                                  int32_t hp);
+/* ResNet stem in one launch: 7x7 convolution, stride 2, pad 3, of x [N,H,W,3] to 64 channels, + bias, ReLU, then 3x3
+ * max pooling, stride 2, pad 1 -> y [N,P2,Q2,64] (P = (H-1)/2+1, P2 = (P-1)/2+1, likewise Q).  W even.
+ * wf fp16 [64][176]: row k is 22 fragments of 8 halfs; fragment 3r + j holds halfs 8j..8j+7 of the 24-half window
+ * of filter row r, {0, w[k][r][0][c=0..2], w[k][r][1][0..2], ..., w[k][r][6][0..2], 0, 0} (w indexed [k][r][s][c]);
+ * the 22nd fragment is zero.  bias fp32 [64]. */
+strait_status strait_k_stem_pool(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf,
+                                 const float* bias, void* y, int32_t hp);
 /* Max pooling 2x2, stride 2, no padding; C % 8 == 0, H and W even. */
 strait_status strait_k_maxpool2x2s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                     void* y, int32_t hp);

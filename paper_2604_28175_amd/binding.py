@@ -87,6 +87,7 @@ _SIGS = {
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
+    "strait_k_stem_pool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _i32]),
     "strait_k_maxpool2x2s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_vit_tokens": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_global_avgpool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _i32]),
@@ -360,6 +361,16 @@ def k_maxpool3x3s2(x, hp=0, stream=None):
     n, h, w, c = x.shape
     y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=torch.float16, device=x.device)
     _check(lib.strait_k_maxpool3x3s2(_stream(stream), _dev(x), n, h, w, c, _dev(y), hp))
+    return y
+
+
+def k_stem_pool(x, wf, bias, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    assert c == 3
+    p, q = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    y = torch.empty((n, (p - 1) // 2 + 1, (q - 1) // 2 + 1, 64), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_stem_pool(_stream(stream), _dev(x), n, h, w, _dev(wf), _dev(bias), _dev(y), hp))
     return y
 
 

@@ -569,6 +569,10 @@ strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t
 strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
     return launch_maxpool3x3s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
 }
+strait_status strait_k_stem_pool(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
+                                 void* y, int32_t hp) {
+    return launch_stem_pool((const half_t*)x, (const half_t*)wf, bias, N, H, W, (half_t*)y, hp, (hipStream_t)stream);
+}
 strait_status strait_k_maxpool2x2s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
     return launch_maxpool2x2s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
 }

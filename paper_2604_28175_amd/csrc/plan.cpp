@@ -172,6 +172,34 @@ struct Loader {
         op.info.weight_bytes = (int64_t)K * C * R * S * 2 + K * 4;
         return 0;
     }
+    // Fused stem + pooling: OIHW [64][3][7][7] -> [64][22 fragments][8]; fragment 3r + j = halfs 8j..8j+7 of filter
+    // row r's window {0, (s=0: c=0,1,2), ..., (s=6: c=0,1,2), 0, 0}; the 22nd fragment stays zero.
+    int stempool_weights(const std::string& name, bool bn, Op& op) {
+        const unsigned K = 64, C = 3, R = 7, S = 7;
+        const TensorView* w = c.find(name + ".w");
+        if (!w) return STRAIT_E_FORMAT;
+        if (!shape_is(w, {K, C, R, S})) { set_error("'%s.w': expected [%u,%u,%u,%u]", name.c_str(), K, C, R, S); return STRAIT_E_FORMAT; }
+        std::vector<float> scale, bias;
+        int rc = scale_bias(name, bn, K, scale, bias);
+        if (rc) return rc;
+        const unsigned ldw = 22 * 8;
+        std::vector<half_t> out((size_t)K * ldw, (half_t)0);
+        for (unsigned k = 0; k < K; ++k)
+            for (unsigned r = 0; r < R; ++r)
+                for (unsigned s = 0; s < S; ++s)
+                    for (unsigned cc = 0; cc < C; ++cc) {
+                        const float v = (float)w->data[((k * C + cc) * R + r) * S + s];
+                        out[(size_t)k * ldw + r * 24 + 1 + s * 3 + cc] = bn ? (half_t)(v * scale[k]) : (half_t)v;
+                    }
+        void *dw = nullptr, *db = nullptr;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bias.data(), bias.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.ldw = (int)ldw;
+        op.info.weight_bytes = (int64_t)K * C * R * S * 2 + K * 4;
+        return 0;
+    }
     // depthwise [C][1][3][3] -> [3][3][C]
     int dw_weights(const std::string& name, unsigned C, Op& op) {
         const TensorView* w = c.find(name + ".w");
@@ -322,6 +350,26 @@ struct Builder {
         return 0;
     }
 
+    // ResNet's 7x7/2 stem convolution (+ ReLU) and the 3x3/2 max pooling behind it as one launch
+    int stem_pool(const std::string& name, bool bn, int H, int W, int* out_slot, int* P_out, int* Q_out) {
+        const int P = osz(H, 7, 2, 3), Q = osz(W, 7, 2, 3), P2 = osz(P, 3, 2, 1), Q2 = osz(Q, 3, 2, 1);
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_STEMPOOL;
+        op.in = SLOT_INPUT;
+        op.H = H; op.W = W; op.C = 3; op.K = 64; op.R = op.S = 7; op.stride = 2; op.pad = 3; op.act = ACT_RELU;
+        op.P = P2; op.Q = Q2;
+        int rc = ld.stempool_weights("stem", bn, op);
+        if (rc) return rc;
+        op.out = pl.get((size_t)P2 * Q2 * 64);
+        op.info.macs_per_sample = (int64_t)P * Q * 64 * 7 * 7 * 3;
+        op.info.bytes_per_sample = 2LL * ((int64_t)H * W * 3 + (int64_t)P2 * Q2 * 64);
+        op.info.gemm_m_per_sample = P * Q; op.info.gemm_n = 64; op.info.gemm_k = 7 * 24;
+        m.ops.push_back(op);
+        *out_slot = op.out; *P_out = P2; *Q_out = Q2;
+        return 0;
+    }
+
     int dwconv(const std::string& name, int in, int H, int W, int C, int stride, int out, int* P_out, int* Q_out) {
         Op op;
         name_op(op, name, 1);
@@ -424,8 +472,12 @@ static int plan_tiny_cnn(Model& m, Builder& b) {
 static int plan_resnet50(Model& m, Builder& b) {
     const int H = m.hyper[0], W = m.hyper[1], C = m.hyper[2], classes = m.hyper[3];
     int cur, P, Q, rc;
-    if ((rc = b.stem("stem", true, H, W, C, 64, 7, 2, 3, ACT_RELU, 0, &cur, &P, &Q))) return rc;
-    {
+    if (C == 3 && W % 2 == 0) {
+        // one launch reads the image and writes the pooled feature map (the layer carries the pooling's name: that is
+        // the activation it produces)
+        if ((rc = b.stem_pool("maxpool", true, H, W, &cur, &P, &Q))) return rc;
+    } else {
+        if ((rc = b.stem("stem", true, H, W, C, 64, 7, 2, 3, ACT_RELU, 0, &cur, &P, &Q))) return rc;
         const int P2 = b.osz(P, 3, 2, 1), Q2 = b.osz(Q, 3, 2, 1);
         const int o = b.pl.get((size_t)P2 * Q2 * 64);
         b.pool("maxpool", POOL_MAX3X3S2, cur, P, Q, 64, o);
@@ -858,6 +910,9 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 rc = launch_conv(p, stream);
                 break;
             }
+            case OP_STEMPOOL:
+                rc = launch_stem_pool((const half_t*)src, op.w, op.bias, batch, op.H, op.W, (half_t*)dst, hp, stream);
+                break;
             case OP_PACK:
                 rc = launch_pack_input((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, op.Hp, op.Wp, op.Cpad, op.pad, op.pad, hp, stream);
                 break;

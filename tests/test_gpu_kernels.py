@@ -171,6 +171,27 @@ def test_attention(S, B, Sq, heads, lens):
         assert np.array_equal(out2[b, :vl[b]], out[b, :vl[b]])
 
 
+def stem_pool_weights(w_oihw):
+    """[64,3,7,7] -> the fused stem kernel's [64][176] layout (strait.h, strait_k_stem_pool)."""
+    wf = np.zeros((64, 22 * 8), np.float16)
+    for r in range(7):
+        for s in range(7):
+            for c in range(3):
+                wf[:, r * 24 + 1 + s * 3 + c] = w_oihw[:, c, r, s]
+    return wf
+
+
+@pytest.mark.parametrize("n,h,w", [(2, 64, 64), (1, 224, 224), (3, 50, 38), (2, 7, 8), (1, 33, 66), (2, 1, 2), (1, 130, 226)])
+def test_stem_pool(S, n, h, w):
+    x = f16(R.standard_normal((n, h, w, 3)))
+    wt = f16(R.standard_normal((64, 3, 7, 7)) * (2.0 / 147) ** 0.5)
+    b = (R.standard_normal(64) * 0.5).astype(np.float32)
+    ref = ops.maxpool2d(ops.relu(ops.conv2d(x, wt, b, 2, 3)), 3, 2, 1)
+    y = S.k_stem_pool(dev(S, x), dev(S, stem_pool_weights(wt)), dev(S, b)).float().cpu().numpy()
+    assert y.shape == ref.shape
+    check_kernel(y, ref, f"stem+pool {n}x{h}x{w}")
+
+
 @pytest.mark.parametrize("n,h,w,c", [(2, 8, 6, 16), (3, 14, 14, 512), (1, 224, 224, 64)])
 def test_maxpool2x2(S, n, h, w, c):
     x = f16(R.standard_normal((n, h, w, c)))
