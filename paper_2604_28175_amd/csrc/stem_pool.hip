@@ -9,7 +9,7 @@
 // A workgroup (4 wavefronts) produces 8 x 7 pooled positions of one image at a time and walks over tiles in
 // a grid-stride loop (the 64 x 176 weight matrix stays in registers across tiles):
 //   1. the 39 x 35-pixel input patch the tile depends on goes to LDS as it lies in memory (3 halfs per pixel),
-//      zeros outside the image;
+//      zeros outside the image; it was fetched into registers while the previous tile was being computed;
 //   2. the 17 x 15 convolution positions under the tile are 8 blocks of 32 rows of an implicit GEMM whose
 //      reduction runs over 7 filter rows x 24 halfs: the 21 halfs of a filter row's 7 taps are contiguous in
 //      the patch, preceded by one half and followed by two that meet zero weights, which makes every 8-half
@@ -39,7 +39,7 @@ constexpr int SP_LDC = 72;                                // convolution tile pi
 constexpr int SP_K = 64;                                  // output channels
 constexpr int SP_STEPS = 11;                              // MFMA steps of 16: 22 fragments of 8 (21 in use)
 
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, 2)
 stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, const float* __restrict__ bias, int N, int H, int W,
                  int P, int Q, int P2, int Q2, int tiles_p, int tiles_q, half_t* __restrict__ y, int hp) {
     __shared__ __attribute__((aligned(16))) uint32_t patch[SP_IR * SP_ROW_DW];
@@ -47,48 +47,85 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
     if (hp) __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
 
+    __shared__ __attribute__((aligned(16))) float bias_s[SP_K];
+    if (tid < SP_K) bias_s[tid] = bias[tid];          // visible after the first barrier of the tile loop
     half8 wreg[2][SP_STEPS];
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int t = 0; t < SP_STEPS; ++t) wreg[ni][t] = *(const half8*)(wf + (ni * 32 + l32) * (SP_STEPS * 16) + (2 * t + lh) * 8);
+        for (int t = 0; t < SP_STEPS; ++t) {
+            wreg[ni][t] = *(const half8*)(wf + (ni * 32 + l32) * (SP_STEPS * 16) + (2 * t + lh) * 8);
+            // Keep the fragment in registers: re-loading it inside the tile loop would put a wait for all older loads,
+            // the prefetched patch among them, in front of every MFMA.
+            asm volatile("" : "+v"(wreg[ni][t]));
+        }
 
-    const long long total = (long long)N * tiles_p * tiles_q;
+    const int total = N * tiles_p * tiles_q;          // the launcher checks that this fits
     const int row_elems = W * 3;
-    for (long long tile = blockIdx.x; tile < total; tile += gridDim.x) {
-        const int tq = (int)(tile % tiles_q);
-        const long long rest = tile / tiles_q;
-        const int tp = (int)(rest % tiles_p), n = (int)(rest / tiles_p);
-        const int P0 = tp * SP_TP, Q0 = tq * SP_TQ;
-        const int ih0 = 4 * P0 - 5, e0 = 12 * Q0 - 16;        // first input row / first (even) element of a row in the patch
+    // Patch traffic: thread (fr, fd) = (tid / 54, tid % 54) of the first 216 moves dword fd of patch rows fr, fr + 4,
+    // ..., so a row step is one pointer increment.  The next tile's patch is fetched into registers while this tile
+    // is computed.
+    constexpr int SP_NF = (SP_IR + 3) / 4;                 // 10 rows per thread (the last pass covers 3 rows)
+    const int fr = tid / SP_USED_DW, fd = tid - fr * SP_USED_DW;
+    const bool mover = tid < 4 * SP_USED_DW;
+    uint32_t pre[SP_NF], pre_in = 0;
+    auto fetch_patch = [&](int tile) {
+        pre_in = 0;
+        const int tq = tile % tiles_q, rest = tile / tiles_q;
+        const int tp = rest % tiles_p, n = rest / tiles_p;
+        const int ih0 = 4 * tp * SP_TP - 5 + fr;           // first input row of this thread
+        const int e = 12 * tq * SP_TQ - 16 + 2 * fd;       // its (even) element within an image row
+        const bool col_in = mover && e >= 0 && e < row_elems;
         const half_t* img = x + (long long)n * H * row_elems;
-
-        for (int idx = tid; idx < SP_IR * SP_USED_DW; idx += 256) {
-            const int row = idx / SP_USED_DW, dw = idx - row * SP_USED_DW;
-            const int ih = ih0 + row, e = e0 + 2 * dw;
-            uint32_t v = 0;
-            if ((unsigned)ih < (unsigned)H && e >= 0 && e < row_elems) v = *(const uint32_t*)(img + (long long)ih * row_elems + e);
-            patch[row * SP_ROW_DW + dw] = v;
+        const half_t* src = img + (long long)ih0 * row_elems + e;
+#pragma unroll
+        for (int i = 0; i < SP_NF; ++i) {
+            const int ih = ih0 + 4 * i;
+            // every lane loads (the image's first dword when its element lies outside) and then selects: no branches
+            const bool in = col_in && (unsigned)ih < (unsigned)H && (4 * i + fr) < SP_IR;
+            pre[i] = *(const uint32_t*)(in ? src + (long long)(4 * i) * row_elems : img);
+            pre_in |= in ? 1u << i : 0u;       // the selection waits until the value is used, one tile later
+        }
+    };
+    if ((int)blockIdx.x < total) fetch_patch((int)blockIdx.x);
+    uint32_t* const pdst = patch + fr * SP_ROW_DW + fd;
+    for (int tile = (int)blockIdx.x; tile < total; tile += (int)gridDim.x) {
+        const int tq = tile % tiles_q, rest = tile / tiles_q;
+        const int tp = rest % tiles_p, n = rest / tiles_p;
+        const int P0 = tp * SP_TP, Q0 = tq * SP_TQ;
+        if (mover) {
+#pragma unroll
+            for (int i = 0; i < SP_NF; ++i)
+                if (4 * i + fr < SP_IR) pdst[4 * i * SP_ROW_DW] = (pre_in >> i & 1u) ? pre[i] : 0u;
         }
         __syncthreads();
+        if (tile + (int)gridDim.x < total) fetch_patch(tile + (int)gridDim.x);
 
 #pragma unroll 1
         for (int mi = 0; mi < 2; ++mi) {
             const int pos = (wave + 4 * mi) * 32 + l32;
             const int pc = pos < SP_POS ? pos : SP_POS - 1;
             const int cr = pc / SP_CC, cc = pc - cr * SP_CC;
+            // Fragment 2t + lh = (filter row, third of its 24 halfs).  The upper half-wave reads the fragment after the
+            // lower one's: 4 dwords further on in the same filter row, or at the start of the next one (56 - 8 dwords
+            // further); the 22nd fragment meets zero weights and re-reads the 21st.  Three lane-dependent bases, and every
+            // step's own offset is a constant.
             const uint32_t* abase = patch + (2 * cr) * SP_ROW_DW + 3 * cc;
+            const uint32_t* base_same = abase + (lh ? 4 : 0);
+            const uint32_t* base_next = abase + (lh ? SP_ROW_DW - 8 : 0);
             floatx16 acc[2];
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[ni][v] = 0.f;
+                for (int g = 0; g < 4; ++g) {          // the accumulators start from the bias
+                    const float4 b4 = *(const float4*)(bias_s + ni * 32 + 8 * g + 4 * lh);
+                    acc[ni][4 * g + 0] = b4.x; acc[ni][4 * g + 1] = b4.y; acc[ni][4 * g + 2] = b4.z; acc[ni][4 * g + 3] = b4.w;
+                }
 #pragma unroll
             for (int t = 0; t < SP_STEPS; ++t) {
-                // fragment 2t + lh = (filter row, third of its 24 halfs); the 22nd fragment meets zero weights
-                const int f0 = 2 * t, f1 = 2 * t + 1 < 21 ? 2 * t + 1 : 20;
-                const int off0 = (f0 / 3) * SP_ROW_DW + (f0 % 3) * 4, off1 = (f1 / 3) * SP_ROW_DW + (f1 % 3) * 4;
-                const uint32_t* ap = abase + (lh ? off1 : off0);
+                const int f0 = 2 * t;
+                const int off0 = (f0 / 3) * SP_ROW_DW + (f0 % 3) * 4;
+                const uint32_t* ap = (t == SP_STEPS - 1 ? abase : (f0 % 3 == 2 ? base_next : base_same)) + off0;
                 const uint32x4 au = {ap[0], ap[1], ap[2], ap[3]};
                 const half8 a = __builtin_bit_cast(half8, au);
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wreg[0][t], a, acc[0], 0, 0, 0);
@@ -96,19 +133,17 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
             }
             const int gr = 2 * P0 - 1 + cr, gc = 2 * Q0 - 1 + cc;
             const bool ok = pos < SP_POS && (unsigned)gr < (unsigned)P && (unsigned)gc < (unsigned)Q;
+            const half4 zero4 = {(half_t)0, (half_t)0, (half_t)0, (half_t)0};
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int c0 = ni * 32 + 8 * g + 4 * lh;
-                    const float4 b4 = *(const float4*)(bias + c0);
                     half4 h;
-                    h[0] = (half_t)fmaxf(acc[ni][4 * g + 0] + b4.x, 0.f);
-                    h[1] = (half_t)fmaxf(acc[ni][4 * g + 1] + b4.y, 0.f);
-                    h[2] = (half_t)fmaxf(acc[ni][4 * g + 2] + b4.z, 0.f);
-                    h[3] = (half_t)fmaxf(acc[ni][4 * g + 3] + b4.w, 0.f);
-                    if (!ok) h = half4{(half_t)0, (half_t)0, (half_t)0, (half_t)0};
-                    *(half4*)(ctile + pos * SP_LDC + c0) = h;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) h[j] = (half_t)acc[ni][4 * g + j];
+                    h = __builtin_elementwise_max(h, zero4);        // ReLU after rounding gives the same fp16 value
+                    if (!ok) h = zero4;
+                    *(half4*)(ctile + pos * SP_LDC + ni * 32 + 8 * g + 4 * lh) = h;
                 }
         }
         __syncthreads();
@@ -119,17 +154,18 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
             const int gp = P0 + pp, gq = Q0 + pq;
             if (gp < P2 && gq < Q2) {
                 const half_t* src = ctile + ((2 * pp) * SP_CC + 2 * pq) * SP_LDC + c8 * 8;
-                half8 m = *(const half8*)src;
+                half8 v[9];
 #pragma unroll
-                for (int dr = 0; dr < 3; ++dr)
+                for (int k = 0; k < 9; ++k) v[k] = *(const half8*)(src + ((k / 3) * SP_CC + k % 3) * SP_LDC);
+                half8 m = v[0];
 #pragma unroll
-                    for (int dc = 0; dc < 3; ++dc)
-                        if (dr | dc) m = __builtin_elementwise_max(m, *(const half8*)(src + (dr * SP_CC + dc) * SP_LDC));
+                for (int k = 1; k < 9; ++k) m = __builtin_elementwise_max(m, v[k]);
                 *(half8*)(y + (((long long)n * P2 + gp) * Q2 + gq) * SP_K + c8 * 8) = m;
             }
         }
-        // The next tile's fill touches only `patch`, which nobody reads between the barrier above and the one after
-        // the fill; `ctile` is rewritten only after that second barrier, when every thread has left the pooling loop.
+        // The next tile's patch is written to LDS after this point: nobody reads `patch` between the barrier above and
+        // the one after that write; `ctile` is rewritten only after that second barrier, when every thread has left
+        // the pooling loop.
     }
 }
 
@@ -141,7 +177,7 @@ int launch_stem_pool(const half_t* x, const half_t* wf, const float* bias, int N
     const int tiles_p = (P2 + SP_TP - 1) / SP_TP, tiles_q = (Q2 + SP_TQ - 1) / SP_TQ;
     const long long total = (long long)N * tiles_p * tiles_q;
     if ((long long)H * W * 3 > 0x7fffffffLL || total > 0x7fffffffLL) { set_error("stem+pool: image or grid too large"); return -5; }
-    const unsigned blocks = (unsigned)(total < 768 ? total : 768);     // 3 workgroups on each of 256 compute units
+    const unsigned blocks = (unsigned)(total < 512 ? total : 512);     // 2 workgroups on each of 256 compute units
     hipLaunchKernelGGL(stem_pool_kernel, dim3(blocks), dim3(256), 0, stream, x, wf, bias, N, H, W, P, Q, P2, Q2, tiles_p, tiles_q, y, hp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("stem+pool launch: %s", hipGetErrorString(e)); return -2; }
