@@ -4,10 +4,11 @@
 //
 //   out[b, i, h*64 + :] = softmax_j( q_i . k_j / sqrt(64) ,  j < valid_len[b] ) @ V
 //
-// One workgroup (4 wavefronts) per (sequence, head, block of 128 queries); wavefront w owns query rows
-// 128*blockIdx.y + 32w .. +31.  Sequences of up to 128 keys keep 4 key blocks of scores in registers, up to
-// 256 keys 8 (a Vision Transformer's 197 tokens); S need not be a multiple of anything: query rows at or
-// beyond S are neither read nor written, key rows at or beyond valid_len never leave zero-filled LDS.
+// One workgroup per (sequence, head); wavefront w owns query rows 32w .. 32w+31.  Sequences of up to 128 keys
+// run 4 wavefronts and keep 4 key blocks of scores in registers, up to 256 keys 8 wavefronts and 8 blocks (a
+// Vision Transformer's 197 tokens), so K and V are staged once per head whatever the length; S need not be a
+// multiple of anything: query rows at or beyond S are neither read nor written, key rows at or beyond
+// valid_len never leave zero-filled LDS.
 //   - K is staged in LDS as [key][d] and V transposed as [d][key], rows at or beyond
 //     valid_len zero-filled, so masked keys can never inject non-finite values;
 //   - scores^T = K Q^T with v_mfma_f32_32x32x16_f16 (K rows are the "A" operand), which leaves
@@ -30,8 +31,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int ATT_D = 64;
 constexpr int ATT_LDK = ATT_D + 8;       // K tile row pitch (halfs)
 
-template <int NKB>                       // key blocks of 32 held in registers: sequences of up to 32 * NKB keys
-__global__ void __launch_bounds__(256) attention_kernel(const half_t* __restrict__ qkv, const int32_t* __restrict__ valid_len,
+template <int NKB>                       // key blocks of 32 held in registers = wavefronts: sequences of up to 32 * NKB keys
+__global__ void __launch_bounds__(64 * NKB) attention_kernel(const half_t* __restrict__ qkv, const int32_t* __restrict__ valid_len,
                                                          int S, int heads, half_t* __restrict__ out, int hp) {
     constexpr int ATT_SMAX = 32 * NKB;
     constexpr int ATT_LDV = ATT_SMAX + 8;    // V^T tile row pitch (halfs)
@@ -50,7 +51,7 @@ __global__ void __launch_bounds__(256) attention_kernel(const half_t* __restrict
     const int tid = threadIdx.x;
     const int nkb = (L + 31) >> 5;          // key blocks that hold at least one valid key
     // ---- stage K and V^T: every row of the key blocks in use, zeros at and beyond valid_len ----
-    for (int id = tid; id < nkb * 32 * 8; id += 256) {
+    for (int id = tid; id < nkb * 32 * 8; id += 64 * NKB) {
         const int key = id >> 3, c8 = id & 7;
         half8 kv, vv;
 #pragma unroll
@@ -67,7 +68,7 @@ __global__ void __launch_bounds__(256) attention_kernel(const half_t* __restrict
 
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int q0 = blockIdx.y * 128 + wave * 32;
+    const int q0 = wave * 32;
     if (q0 >= S) return;
     const bool row_ok = q0 + l32 < S;       // a ragged last block: rows at or beyond S are not written
     half_t* orow = out + ((long long)b * S + q0 + l32) * hidden + h * ATT_D;
@@ -164,7 +165,7 @@ int launch_attention(const half_t* qkv, const int32_t* valid_len, int B, int S, 
     if (!qkv || !valid_len || !out || B <= 0 || heads <= 0) { set_error("attention: invalid arguments"); return -1; }
     if (S <= 0 || S > 256) { set_error("attention: sequence length %d must be in 1..256", S); return -5; }
     if ((long long)B * heads > 0x7fffffffLL) { set_error("attention: grid too large"); return -5; }
-    const dim3 grid((unsigned)(B * heads), (unsigned)((S + 127) / 128));
+    const dim3 grid((unsigned)(B * heads));
     auto lds_bytes = [](int nkb) { return (size_t)(32 * nkb * ATT_LDK + ATT_D * (32 * nkb + 8)) * sizeof(half_t); };
     if (S <= 128) {
         hipLaunchKernelGGL(attention_kernel<4>, grid, dim3(256), lds_bytes(4), stream, qkv, valid_len, S, heads, out, hp);
@@ -176,7 +177,7 @@ int launch_attention(const half_t* qkv, const int32_t* valid_len, int B, int S, 
             if (ea != hipSuccess) { set_error("attention: hipFuncSetAttribute: %s", hipGetErrorString(ea)); return -2; }
             configured.store(true, std::memory_order_release);
         }
-        hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(256), lds_bytes(8), stream, qkv, valid_len, S, heads, out, hp);
+        hipLaunchKernelGGL(attention_kernel<8>, grid, dim3(512), lds_bytes(8), stream, qkv, valid_len, S, heads, out, hp);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("attention launch: %s", hipGetErrorString(e)); return -2; }
