@@ -51,18 +51,26 @@ __global__ void __launch_bounds__(64 * NKB) attention_kernel(const half_t* __res
     const int tid = threadIdx.x;
     const int nkb = (L + 31) >> 5;          // key blocks that hold at least one valid key
     // ---- stage K and V^T: every row of the key blocks in use, zeros at and beyond valid_len ----
-    for (int id = tid; id < nkb * 32 * 8; id += 64 * NKB) {
-        const int key = id >> 3, c8 = id & 7;
-        half8 kv, vv;
+    // a thread moves 8 features of two neighbouring keys: the transposed V tile is then written two keys (one dword)
+    // at a time
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    for (int id = tid; id < nkb * 16 * 8; id += 64 * NKB) {
+        const int key = (id >> 3) * 2, c8 = id & 7;
+        half8 k0, k1, v0, v1;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { kv[j] = (half_t)0; vv[j] = (half_t)0; }
+        for (int j = 0; j < 8; ++j) { k0[j] = k1[j] = v0[j] = v1[j] = (half_t)0; }
         if (key < L) {
-            kv = *(const half8*)(base + key * row_pitch + hidden + c8 * 8);
-            vv = *(const half8*)(base + key * row_pitch + 2 * hidden + c8 * 8);
+            k0 = *(const half8*)(base + key * row_pitch + hidden + c8 * 8);
+            v0 = *(const half8*)(base + key * row_pitch + 2 * hidden + c8 * 8);
         }
-        *(half8*)(Ks + key * ATT_LDK + c8 * 8) = kv;
+        if (key + 1 < L) {
+            k1 = *(const half8*)(base + (key + 1) * row_pitch + hidden + c8 * 8);
+            v1 = *(const half8*)(base + (key + 1) * row_pitch + 2 * hidden + c8 * 8);
+        }
+        *(half8*)(Ks + key * ATT_LDK + c8 * 8) = k0;
+        *(half8*)(Ks + (key + 1) * ATT_LDK + c8 * 8) = k1;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) Vt[(c8 * 8 + j) * ATT_LDV + key] = vv[j];
+        for (int j = 0; j < 8; ++j) *(half2v*)(Vt + (c8 * 8 + j) * ATT_LDV + key) = half2v{v0[j], v1[j]};
     }
     __syncthreads();
 
