@@ -158,7 +158,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=0, help="images the CPU oracle is timed on (0 = twelve per thread)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the served path has no collectives); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library serves from one GPU (the served path has no collectives); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
