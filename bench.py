@@ -225,6 +225,20 @@ def main() -> int:
     dt, dev_ms = timed(model, B, K, W)
     value = K * B / dt
 
+    # clock and power while the same steps run (a second, untimed pass: the query itself takes about as long as K steps)
+    def gpu_state_under_load():
+        import subprocess
+        try:
+            for _ in range(3 * K):
+                model.run(0, prio, B)
+            r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=20)
+            torch.cuda.synchronize()
+            card = next(iter(json.loads(r.stdout[r.stdout.index("{"):]).values()))
+            return {k.strip(": ").replace(" ", "_"): v for k, v in card.items()}
+        except Exception as e:                    # no such tool, no permission, unexpected format: the figure is optional
+            torch.cuda.synchronize()
+            return {"unavailable": type(e).__name__}
+
     # ---- roofline of the dominant kernel (implicit-GEMM convolution), per-layer event pairs
     layers = model.layers()
     ms = np.zeros(len(layers))
@@ -260,6 +274,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "gpu_state_under_load": gpu_state_under_load(),
         "config": {"workload": f"resnet50_v1.5 224x224 fp16 NHWC, batch {B}, BatchNorm folded, input resident in HBM",
                    "batch": B, "priority": "high"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
