@@ -232,3 +232,38 @@ def test_argument_checks(S):
         srv.request(1, None, None)                                 # not started
     srv.close()
     sched.close()
+
+
+def test_requests_from_many_threads(S):
+    """strait_server_request is thread-safe: eight producers, every request accounted for exactly once."""
+    gpu = FakeGpu({1: 2, 2: 3})
+    sched, srv = make(S, gpu, {1: (HIGH, 8, 2000, 1, 2, 2), 2: (LOW, 8, 2000, 2, 2, 3)})
+    ids, lock = [], threading.Lock()
+
+    def producer(k):
+        mine = [srv.request(1 + (k + i) % 2, None, None) for i in range(100)]
+        with lock:
+            ids.extend(mine)
+
+    th = [threading.Thread(target=producer, args=(k,)) for k in range(8)]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    recs, st = finish(sched, srv)
+    assert len(set(ids)) == 800 and sorted(r.request_id for r in recs) == sorted(ids)
+    assert st.requests == 800 == st.served + st.dropped + st.failed
+
+
+def test_stop_lets_batches_in_flight_finish(S):
+    gpu = FakeGpu({1: 80})
+    sched, srv = make(S, gpu, {1: (HIGH, 1, 5000, 0, 2, 80)}, concurrency=2)
+    a, b, c = (srv.request(1, None, None) for _ in range(3))      # two start at once, the third waits for an instance
+    time.sleep(0.02)
+    t0 = time.monotonic()
+    srv.stop()                                                     # returns only when the two running batches are done
+    assert time.monotonic() - t0 >= 0.04
+    recs = {r.request_id: r for r in srv.results()}
+    assert recs[a].status == 0 and recs[b].status == 0 and recs[c].status == 3 and gpu.live == 0
+    srv.close()
+    sched.close()
