@@ -136,6 +136,52 @@ def serving(ctx, md_resnet, blob_resnet, seconds, hp_rate, lp_rate):
     return res
 
 
+def serving_mixed(models_data, seconds, scale):
+    """The paper's heterogeneous workload by shape (Table 1: model, priority, deadline) on one GPU: ResNet-50 (high,
+    8 ms), ViT-B/16 (high, 15 ms), VGG-19 (low, 25 ms) and a BERT-base-shaped encoder standing in for RoBERTa-B
+    (low, 45 ms), single requests on independent Poisson schedules, maximum batch 8, four batches in flight, batch
+    formation timeout a tenth of the deadline (Section 5.1)."""
+    import synth
+    import paper_2604_28175_amd as strait
+    from paper_2604_28175_amd import serve
+
+    seed = synth.SEEDS["colocation"] + 11
+    table = {1: ("resnet50", synth.ARCH_RESNET50, strait.PRIO_HIGH, 8.0, 2000.0),
+             2: ("vit_b16", synth.ARCH_VIT, strait.PRIO_HIGH, 15.0, 1200.0),
+             3: ("vgg19", synth.ARCH_VGG19, strait.PRIO_LOW, 25.0, 1200.0),
+             4: ("encoder", synth.ARCH_ENCODER, strait.PRIO_LOW, 45.0, 1500.0)}
+    # four batches in flight need four compute streams to run side by side: two per priority level
+    ctx = strait.Context(device=0, n_hp=2, n_lp=2, n_copy=2)
+    sched = strait.Scheduler(1)
+    srv = strait.Server(sched, 4, 200_000)
+    ctx.set_graphs(True)
+    loaded, streams = {}, {}
+    for mid, (name, arch, prio, deadline_ms, rate) in table.items():
+        md, blob = models_data(arch)
+        m = ctx.load(blob, max_batch=8, n_instances=3)
+        loaded[mid] = m
+        sched.set_profile(mid, prio, serve.profile_tuples(serve.offline_profiles(m, prio, 8, reps=20)))
+        srv.add_model(m, mid, prio, 8, int(deadline_ms * 1e6), int(deadline_ms * 1e5))
+        if arch == synth.ARCH_ENCODER:
+            xs, _ = synth.token_batch(md, 8, seed + mid)
+            streams[mid] = {"model": m, "inputs": list(xs), "valid_len": 96}
+        else:
+            streams[mid] = {"model": m, "inputs": list(synth.default_image_batch(md, 8, seed + mid))}
+        streams[mid]["arrivals_ns"] = synth.poisson_arrivals_ns(seed + mid, rate * scale, seconds)
+    srv.start()
+    summ = serve.run_open_loop(srv, streams, seconds)
+    st = srv.stats()
+    srv.close()
+    sched.close()
+    for m in loaded.values():
+        m.free()
+    ctx.close()
+    res = {name: dict(priority="high" if prio == strait.PRIO_HIGH else "low", deadline_ms=deadline_ms, rate_per_s=rate * scale, **summ[mid])
+           for mid, (name, arch, prio, deadline_ms, rate) in table.items()}
+    res.update(seconds=seconds, batches=st.batches, max_in_flight=st.max_in_flight, deferrals=st.deferrals)
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +197,7 @@ def main() -> int:
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
     ap.add_argument("--serving-seconds", type=float, default=3.0,
                     help="seconds per phase of the request-level serving run (0 = skip)")
+    ap.add_argument("--serving-mixed-scale", type=float, default=1.0, help="multiplies the request rates of the four-model serving phase")
     ap.add_argument("--serving-hp-rate", type=float, default=4000.0, help="high-priority requests per second")
     ap.add_argument("--serving-lp-rate", type=float, default=10000.0, help="low-priority requests per second")
     ap.add_argument("--copy-calibration-mb", type=int, default=0,
@@ -194,9 +241,18 @@ def main() -> int:
         torch.cuda.synchronize()
         return time.perf_counter() - t0, ev0.elapsed_time(ev1)
 
+    data_cache = {synth.ARCH_RESNET50: (md, blob)}
+
+    def models_data(arch):
+        """(seeded tensors, weight container) of an architecture, generated once per run."""
+        if arch not in data_cache:
+            amd = synth.make_model(arch, synth.SEEDS[arch])
+            data_cache[arch] = (amd, synth.pack(amd))
+        return data_cache[arch]
+
     def other_model(arch, steps=20, warmup=5):
-        omd = synth.make_model(arch, synth.SEEDS[arch])
-        om = ctx.load(synth.pack(omd), max_batch=64, n_instances=1)
+        omd, oblob = models_data(arch)
+        om = ctx.load(oblob, max_batch=64, n_instances=1)
         om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
         om.sync(0, prio)
         odt, odev = timed(om, 64, steps, warmup)
@@ -356,6 +412,8 @@ def main() -> int:
     if args.serving_seconds > 0:
         out["serving"] = serving(ctx, md, blob, args.serving_seconds, args.serving_hp_rate, args.serving_lp_rate)
     ctx.close()
+    if args.serving_seconds > 0 and not args.no_other_models:
+        out["serving_mixed"] = serving_mixed(models_data, args.serving_seconds, args.serving_mixed_scale)
 
     if not args.no_cpu_baseline:
         from oracle import models as omodels
