@@ -377,6 +377,26 @@ def main() -> int:
         torch.cuda.synchronize()
         out["two_instances"] = {"images_per_s": round(K * B / (time.perf_counter() - t0), 1), "steps": K,
                                 "note": "K steps alternating between two instances on two streams"}
+        by2 = {}
+        for b in (32, 8, 1):                       # the smaller batch sizes the same way: small batches gain most
+            if b >= B:
+                continue
+            xb = synth.default_image_batch(md, b, seed + b)
+            for inst, pr in ((0, strait.PRIO_HIGH), (1, strait.PRIO_LOW)):
+                pair.copy_in(inst, pr, xb)
+                pair.sync(inst, pr)
+            kb = 2 * max(K, 100)
+            for phase_steps in (20, kb):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for k in range(phase_steps):
+                    pair.run(k & 1, strait.PRIO_HIGH if (k & 1) == 0 else strait.PRIO_LOW, b)
+                torch.cuda.synchronize()
+            by2[str(b)] = round(kb * b / (time.perf_counter() - t0), 1)
+        out["two_instances"]["by_batch"] = by2
+        for inst, pr in ((0, strait.PRIO_HIGH), (1, strait.PRIO_LOW)):
+            pair.copy_in(inst, pr, x)
+            pair.sync(inst, pr)
         # end to end: the batch waits in pinned host memory; submit -> H2D on a copy stream -> kernels -> D2H, two
         # instances double-buffering (the copy of one batch runs beside the kernels of the other)
         stage = [pair.staging(i, B) for i in range(2)]
