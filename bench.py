@@ -190,6 +190,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-batch", action="store_true")
+    ap.add_argument("--no-gpu-state", action="store_true", help="skip the extra passes during which clocks are read (profiling runs count passes)")
     ap.add_argument("--no-other-models", action="store_true", help="skip the VGG-19 and ViT-B/16 throughput lines")
     ap.add_argument("--only-model", choices=("vgg19", "vit_b16"), default=None,
                     help="time nothing but this model at batch 64 (for kernel profiles of the second workload set)")
@@ -330,7 +331,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(dt / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "gpu_state_under_load": gpu_state_under_load(),
+        "gpu_state_under_load": None if args.no_gpu_state else gpu_state_under_load(),
         "config": {"workload": f"resnet50_v1.5 224x224 fp16 NHWC, batch {B}, BatchNorm folded, input resident in HBM",
                    "batch": B, "priority": "high"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
