@@ -84,6 +84,7 @@ struct strait_server {
     strait_server_stats stats{};
     int in_flight = 0;
     bool running = false, stopping = false, kick = false;
+    bool sched_done = false;                  // the scheduling thread has ended: no batch will be dispatched any more
     uint64_t next_req = 1, next_batch = 1;
     int64_t last_h2d_end = 0;
     std::thread sched_th;
@@ -285,7 +286,7 @@ struct strait_server {
             Batch* b = nullptr;
             {
                 std::unique_lock<std::mutex> lk(mu);
-                cv_exec.wait(lk, [&] { return !dispatched.empty() || (stopping && in_flight == 0); });
+                cv_exec.wait(lk, [&] { return !dispatched.empty() || (sched_done && in_flight == 0); });
                 if (dispatched.empty()) return;
                 b = dispatched.front();
                 dispatched.pop_front();
@@ -495,6 +496,10 @@ strait_status strait_server_stop(strait_server* s) {
     s->cv_sched.notify_all();
     s->cv_exec.notify_all();
     if (s->sched_th.joinable()) s->sched_th.join();   // no batch leaves after this
+    {
+        std::lock_guard<std::mutex> lk(s->mu);
+        s->sched_done = true;                         // only now may idle execution threads end
+    }
     s->cv_exec.notify_all();
     for (auto& th : s->exec_th) if (th.joinable()) th.join();
     s->exec_th.clear();
