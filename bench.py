@@ -400,27 +400,32 @@ def main() -> int:
             pair.sync(inst, pr)
         # end to end: the batch waits in pinned host memory; submit -> H2D on a copy stream -> kernels -> D2H, two
         # instances double-buffering (the copy of one batch runs beside the kernels of the other)
-        stage = [pair.staging(i, B) for i in range(2)]
-        outs = [pair.new_output(B) for _ in range(2)]
-        for i in range(2):
+        pipe = ctx.load(blob, max_batch=B, n_instances=4)
+        stage = [pipe.staging(i, B) for i in range(4)]
+        outs = [pipe.new_output(B) for _ in range(4)]
+        for i in range(4):
             stage[i][:] = x
-        tickets = [None, None]
+        tickets = [None] * 4
         def submit_e2e(k):
-            i = k & 1
+            i = k & 3
             if tickets[i] is not None:
-                pair.wait(tickets[i])
-            tickets[i] = pair.submit(strait.PRIO_HIGH if i == 0 else strait.PRIO_LOW, stage[i], None, outs[i])
-        for k in range(4):
+                pipe.wait(tickets[i])
+            tickets[i] = pipe.submit(strait.PRIO_HIGH if (k & 1) == 0 else strait.PRIO_LOW, stage[i], None, outs[i])
+        def drain():
+            for i in range(4):
+                if tickets[i] is not None:
+                    pipe.wait(tickets[i])
+                    tickets[i] = None
+        for k in range(8):
             submit_e2e(k)
-        for i in range(2):
-            pair.wait(tickets[i]); tickets[i] = None
+        drain()
         t0 = time.perf_counter()
         for k in range(K):
             submit_e2e(k)
-        for i in range(2):
-            pair.wait(tickets[i]); tickets[i] = None
+        drain()
         out["end_to_end"] = {"images_per_s": round(K * B / (time.perf_counter() - t0), 1), "steps": K,
-                             "note": "pinned host input -> H2D -> kernels -> D2H through strait_submit, two instances double-buffering"}
+                             "note": "pinned host input -> H2D -> kernels -> D2H through strait_submit, four instances in rotation on the two compute streams (a batch is resubmitted when its instance's previous batch has completed)"}
+        pipe.free()
         pair.free()
 
     if not args.no_other_models:
