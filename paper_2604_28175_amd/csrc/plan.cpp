@@ -315,7 +315,7 @@ struct Builder {
         (void)out_slot_elems_hint;
         const int Cpad = (stride * 4) % 8 == 0 ? 4 : 8;
         int Sv = R;
-        while ((Sv * Cpad) % 8 != 0) ++Sv;
+        while ((Sv * Cpad) % 32 != 0) ++Sv;       // 32 channels per virtual tap row: the reduction then runs through the LDS-direct kernel
         const int P = osz(H, R, stride, pad), Q = osz(W, R, stride, pad);
         int Hp = std::max(H + 2 * pad, (P - 1) * stride + R);
         int Wp = std::max(W + 2 * pad, (Q - 1) * stride + Sv);
