@@ -574,41 +574,47 @@ int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, in
 
 // ------------------------------------------------------------------------------------------
 // LayerNorm: one wavefront per row, the row held in registers (n <= 8192 -> at most 16 chunks
-// of 8 per lane), two-pass mean / variance in fp32.
-template <int MAXC>
+// of 8 per lane), two-pass mean / variance in fp32.  Rows whose 8-element chunks do not fill 64 lanes evenly but do
+// fill 32 (768 features = 96 chunks) go to half a wavefront each: LPR lanes per row.
+template <int MAXC, int LPR>
 __global__ void __launch_bounds__(256) layernorm_kernel(const half_t* __restrict__ x, const float* __restrict__ gamma,
                                                          const float* __restrict__ beta, int rows, int n, float eps,
                                                          half_t* __restrict__ y, int hp, long long x_row_stride) {
     if (hp) __builtin_amdgcn_s_setprio(3);
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
+    const int lane = threadIdx.x & (LPR - 1);
+    const int row = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+    if (row >= rows) return;                    // whole groups of LPR lanes leave together: the shuffles below stay inside a group
+    auto group_sum = [](float t) {
+#pragma unroll
+        for (int o = LPR / 2; o > 0; o >>= 1) t += __shfl_xor(t, o, 64);
+        return t;
+    };
     const int nch = n >> 3;
     const half_t* src = x + (long long)row * x_row_stride;
     float v[MAXC][8];
     float s = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
-        const int idx = lane + c * 64;
+        const int idx = lane + c * LPR;
         if (idx < nch) {
             const half8 h = *(const half8*)(src + idx * 8);
 #pragma unroll
             for (int j = 0; j < 8; ++j) { v[c][j] = (float)h[j]; s += v[c][j]; }
         }
     }
-    const float mean = wave_sum(s) / (float)n;
+    const float mean = group_sum(s) / (float)n;
     float q = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c)
-        if (lane + c * 64 < nch) {
+        if (lane + c * LPR < nch) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) { const float d = v[c][j] - mean; q += d * d; }
         }
-    const float rstd = 1.f / sqrtf(wave_sum(q) / (float)n + eps);
+    const float rstd = 1.f / sqrtf(group_sum(q) / (float)n + eps);
     half_t* dst = y + (long long)row * n;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
-        const int idx = lane + c * 64;
+        const int idx = lane + c * LPR;
         if (idx < nch) {
             half8 o;
 #pragma unroll
@@ -627,12 +633,14 @@ int launch_layernorm(const half_t* x, const float* gamma, const float* beta, int
     }
     const dim3 grid((rows + 3) / 4), block(256);
     const int nch = n / 8;
-    if (nch <= 128)
-        hipLaunchKernelGGL(layernorm_kernel<2>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
+    if (nch <= 128 && nch % 32 == 0 && nch % 64 != 0)
+        hipLaunchKernelGGL((layernorm_kernel<4, 32>), dim3((rows + 7) / 8), block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
+    else if (nch <= 128)
+        hipLaunchKernelGGL((layernorm_kernel<2, 64>), grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     else if (nch <= 512)
-        hipLaunchKernelGGL(layernorm_kernel<8>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
+        hipLaunchKernelGGL((layernorm_kernel<8, 64>), grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     else
-        hipLaunchKernelGGL(layernorm_kernel<16>, grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
+        hipLaunchKernelGGL((layernorm_kernel<16, 64>), grid, block, 0, stream, x, gamma, beta, rows, n, eps, y, hp, x_row_stride);
     STRAIT_CHECK_LAUNCH("layernorm");
     return 0;
 }

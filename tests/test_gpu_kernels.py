@@ -138,7 +138,7 @@ def test_softmax_top1(S, rows, n):
     assert t.cpu().numpy()[-1] == 0
 
 
-@pytest.mark.parametrize("rows,n", [(7, 768), (130, 768), (3, 64), (2, 3072)])
+@pytest.mark.parametrize("rows,n", [(7, 768), (130, 768), (3, 64), (2, 3072), (5, 256), (13, 512), (9, 1024)])
 def test_layernorm(S, rows, n):
     x = f16(R.standard_normal((rows, n)) * 3 + 1)
     g = R.uniform(0.8, 1.2, n).astype(np.float32)
