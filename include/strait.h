@@ -139,7 +139,7 @@ strait_status strait_model_free(strait_model* m);       /* E_BUSY with batches i
 /* Sizes of one batch's host input and output.
  * CNN input : fp16 [batch][H][W][3].  CNN output: fp32 logits [batch][classes], then fp32
  *             probabilities [batch][classes], then int32 top-1 [batch] (lowest index on ties).
- * Encoder in: fp16 [batch][seq][hidden] (+ int32 valid_len[batch] passed separately);
+ * Encoder in: fp16 [batch][seq][hidden] (seq <= 256, head dimension 64) (+ int32 valid_len[batch] passed separately);
  *        out: fp16 hidden states [batch][seq][hidden], then int32 argmax over the features of
  *             token 0 [batch]. */
 strait_status strait_model_io(const strait_model* m, int32_t batch, size_t* in_bytes, size_t* out_bytes);

@@ -425,6 +425,53 @@ struct Builder {
         return 0;
     }
 
+    // a linear layer applied to every row of a [rows][K] activation per sample (token-wise GEMM); several weight
+    // matrices of the container may be stacked along the output axis (Q | K | V)
+    int token_gemm(const std::string& name, std::initializer_list<std::string> ws, int rows, int in, int K, int N, int act,
+                   int res, int out) {
+        Op op;
+        name_op(op, name, 0);
+        op.kind = OP_CONV;
+        op.in = in; op.out = out; op.res = res; op.act = act;
+        op.P = rows; op.Q = 1; op.H = rows; op.W = 1;
+        op.C = K; op.K = N; op.vC = K; op.vR = op.vS = 1; op.vH = op.vW = 1;
+        op.sN = K; op.sH = K; op.sW = K;
+        unsigned nout = 0;
+        int rc = ld.linear_weights(ws, K, op, &nout);
+        if (rc) return rc;
+        if ((int)nout != N) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), N, nout); return STRAIT_E_FORMAT; }
+        op.info.macs_per_sample = (int64_t)rows * K * N;
+        op.info.bytes_per_sample = 2LL * rows * ((int64_t)K + (int64_t)N * (res != SLOT_NONE ? 2 : 1));
+        op.info.gemm_m_per_sample = rows; op.info.gemm_n = N; op.info.gemm_k = K;
+        m.ops.push_back(op);
+        return 0;
+    }
+
+    // LayerNorm over `width` features of `rows` rows per sample; in_stride: elements between input rows (0 = width)
+    int layer_norm(const std::string& name, int in, int out, int out_ref, int rows, int width, float eps, long long in_stride) {
+        Op op;
+        name_op(op, name, 4);
+        op.kind = OP_LAYERNORM;
+        op.in = in; op.out = out; op.out_ref = out_ref; op.P = rows; op.K = width; op.eps = eps; op.in_row_stride = in_stride;
+        int rc;
+        if ((rc = ld.vector_f32(name + ".g", width, &op.bias))) return rc;
+        if ((rc = ld.vector_f32(name + ".b", width, &op.beta))) return rc;
+        op.info.bytes_per_sample = 4LL * rows * width;
+        op.info.weight_bytes = 8LL * width;
+        m.ops.push_back(op);
+        return 0;
+    }
+
+    void attention(const std::string& name, int qkv, int out, int seq, int heads, int hidden) {
+        Op op;
+        name_op(op, name, 5);
+        op.kind = OP_ATTENTION;
+        op.in = qkv; op.out = out; op.seq = seq; op.heads = heads; op.P = seq; op.K = hidden;
+        op.info.macs_per_sample = 2LL * seq * seq * hidden;
+        op.info.bytes_per_sample = 2LL * seq * hidden * 4;
+        m.ops.push_back(op);
+    }
+
     // FC on a feature vector f [C] (fp32 logits into the output buffer) -> softmax + top-1
     int head(int f, int C, int classes) {
         Op fc;
@@ -623,36 +670,11 @@ static int plan_vit(Model& m, Builder& b) {
     if (seq > 256) { set_error("ViT: %d tokens, at most 256 are supported", seq); return STRAIT_E_SHAPE; }
     m.seq = seq; m.hidden = hidden;
     Loader& ld = b.ld;
-    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) -> int {
-        Op op;
-        name_op(op, name, 0);
-        op.kind = OP_CONV;
-        op.in = in; op.out = out; op.res = res; op.act = act;
-        op.P = seq; op.Q = 1; op.H = seq; op.W = 1;
-        op.C = K; op.K = N; op.vC = K; op.vR = op.vS = 1; op.vH = op.vW = 1;
-        op.sN = K; op.sH = K; op.sW = K;
-        unsigned nout = 0;
-        int rc = ld.linear_weights(ws, K, op, &nout);
-        if (rc) return rc;
-        if ((int)nout != N) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), N, nout); return STRAIT_E_FORMAT; }
-        op.info.macs_per_sample = (int64_t)seq * K * N;
-        op.info.bytes_per_sample = 2LL * seq * ((int64_t)K + (int64_t)N * (res != SLOT_NONE ? 2 : 1));
-        op.info.gemm_m_per_sample = seq; op.info.gemm_n = N; op.info.gemm_k = K;
-        m.ops.push_back(op);
-        return 0;
+    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) {
+        return b.token_gemm(name, ws, seq, in, K, N, act, res, out);
     };
-    auto lnorm = [&](const std::string& name, int in, int out, int rows, long long in_stride) -> int {
-        Op op;
-        name_op(op, name, 4);
-        op.kind = OP_LAYERNORM;
-        op.in = in; op.out = out; op.P = rows; op.K = hidden; op.eps = 1e-6f; op.in_row_stride = in_stride;
-        int rc;
-        if ((rc = ld.vector_f32(name + ".g", hidden, &op.bias))) return rc;
-        if ((rc = ld.vector_f32(name + ".b", hidden, &op.beta))) return rc;
-        op.info.bytes_per_sample = 4LL * rows * hidden;
-        op.info.weight_bytes = 8LL * hidden;
-        m.ops.push_back(op);
-        return 0;
+    auto lnorm = [&](const std::string& name, int in, int out, int rows, long long in_stride) {
+        return b.layer_norm(name, in, out, 0, rows, hidden, 1e-6f, in_stride);
     };
     int patches, P, Q, rc;
     if ((rc = b.stem("patch", false, H, W, C, hidden, 16, 16, 0, ACT_NONE, 0, &patches, &P, &Q))) return rc;
@@ -686,15 +708,7 @@ static int plan_vit(Model& m, Builder& b) {
         if ((rc = gemm(p + ".qkv", {p + ".q", p + ".k", p + ".v"}, n1, hidden, 3 * hidden, ACT_NONE, SLOT_NONE, qkv))) return rc;
         b.pl.put(n1);
         const int att = b.pl.get(tok);
-        {
-            Op op;
-            name_op(op, p + ".attn", 5);
-            op.kind = OP_ATTENTION;
-            op.in = qkv; op.out = att; op.seq = seq; op.heads = heads; op.P = seq; op.K = hidden;
-            op.info.macs_per_sample = 2LL * seq * seq * hidden;
-            op.info.bytes_per_sample = 2LL * seq * hidden * 4;
-            m.ops.push_back(op);
-        }
+        b.attention(p + ".attn", qkv, att, seq, heads, hidden);
         b.pl.put(qkv);
         const int z1 = b.pl.get(tok);
         if ((rc = gemm(p + ".o", {p + ".o"}, att, hidden, hidden, ACT_NONE, z, z1))) return rc;
@@ -721,39 +735,13 @@ static int plan_vit(Model& m, Builder& b) {
 static int plan_encoder(Model& m, Builder& b) {
     const int layers = m.hyper[0], hidden = m.hyper[1], heads = m.hyper[2], ffn = m.hyper[3], seq = m.hyper[4];
     if (heads <= 0 || hidden != heads * 64) { set_error("encoder: head dimension must be 64 (hidden %d, heads %d)", hidden, heads); return STRAIT_E_SHAPE; }
-    if (seq <= 0 || seq > 128 || seq % 32 != 0) { set_error("encoder: sequence length %d must be a multiple of 32, at most 128", seq); return STRAIT_E_SHAPE; }
+    if (seq <= 0 || seq > 256) { set_error("encoder: sequence length %d must be in 1..256", seq); return STRAIT_E_SHAPE; }
     if (ffn % 8 != 0) { set_error("encoder: ffn width must be a multiple of 8"); return STRAIT_E_SHAPE; }
-    Loader& ld = b.ld;
-    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) -> int {
-        Op op;
-        name_op(op, name, 0);
-        op.kind = OP_CONV;
-        op.in = in; op.out = out; op.res = res; op.act = act;
-        op.P = seq; op.Q = 1; op.H = seq; op.W = 1;            // seq rows per sample
-        op.C = K; op.K = N; op.vC = K; op.vR = op.vS = 1; op.vH = op.vW = 1;
-        op.sN = K; op.sH = K; op.sW = K;
-        unsigned nout = 0;
-        int rc = ld.linear_weights(ws, K, op, &nout);
-        if (rc) return rc;
-        if ((int)nout != N) { set_error("'%s': expected %d outputs, container has %u", name.c_str(), N, nout); return STRAIT_E_FORMAT; }
-        op.info.macs_per_sample = (int64_t)seq * K * N;
-        op.info.bytes_per_sample = 2LL * seq * ((int64_t)K + (int64_t)N * (res != SLOT_NONE ? 2 : 1));
-        op.info.gemm_m_per_sample = seq; op.info.gemm_n = N; op.info.gemm_k = K;
-        m.ops.push_back(op);
-        return 0;
+    auto gemm = [&](const std::string& name, std::initializer_list<std::string> ws, int in, int K, int N, int act, int res, int out) {
+        return b.token_gemm(name, ws, seq, in, K, N, act, res, out);
     };
-    auto lnorm = [&](const std::string& name, int in, int out, int out_ref) -> int {
-        Op op;
-        name_op(op, name, 4);
-        op.kind = OP_LAYERNORM;
-        op.in = in; op.out = out; op.out_ref = out_ref; op.P = seq; op.K = hidden; op.eps = 1e-12f;
-        int rc;
-        if ((rc = ld.vector_f32(name + ".g", hidden, &op.bias))) return rc;
-        if ((rc = ld.vector_f32(name + ".b", hidden, &op.beta))) return rc;
-        op.info.bytes_per_sample = 4LL * seq * hidden;
-        op.info.weight_bytes = 8LL * hidden;
-        m.ops.push_back(op);
-        return 0;
+    auto lnorm = [&](const std::string& name, int in, int out, int out_ref) {
+        return b.layer_norm(name, in, out, out_ref, seq, hidden, 1e-12f, 0);
     };
     int x = SLOT_INPUT, rc;
     const size_t tok = (size_t)seq * hidden;
@@ -764,15 +752,7 @@ static int plan_encoder(Model& m, Builder& b) {
         const int qkv = b.pl.get(3 * tok);
         if ((rc = gemm(p + ".qkv", {p + ".q", p + ".k", p + ".v"}, x, hidden, 3 * hidden, ACT_NONE, SLOT_NONE, qkv))) return rc;
         const int att = b.pl.get(tok);
-        {
-            Op op;
-            name_op(op, p + ".attn", 5);
-            op.kind = OP_ATTENTION;
-            op.in = qkv; op.out = att; op.seq = seq; op.heads = heads; op.P = seq; op.K = hidden;
-            op.info.macs_per_sample = 2LL * seq * seq * hidden;
-            op.info.bytes_per_sample = 2LL * seq * hidden * 4;
-            m.ops.push_back(op);
-        }
+        b.attention(p + ".attn", qkv, att, seq, heads, hidden);
         b.pl.put(qkv);
         const int t = b.pl.get(tok);
         if ((rc = gemm(p + ".o", {p + ".o"}, att, hidden, hidden, ACT_NONE, x, t))) return rc;

@@ -93,6 +93,8 @@ def test_mobilenet_v2(ctx, hw, batch):
 
 
 @pytest.mark.parametrize("kw,batch", [(dict(layers=2, hidden=128, heads=2, ffn=256, seq=64), 3),
+                                      (dict(layers=2, hidden=128, heads=2, ffn=256, seq=48), 3),      # no multiple of the 32-row blocks
+                                      (dict(layers=1, hidden=64, heads=1, ffn=128, seq=200), 2),      # more than 128 keys
                                       (dict(), 2)])
 def test_encoder(ctx, kw, batch):
     md = synth.encoder(synth.SEEDS[synth.ARCH_ENCODER], **kw)
