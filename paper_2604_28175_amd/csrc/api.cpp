@@ -198,6 +198,7 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
     for (Instance& in : m->inst) {
         bool ok = hipHostMalloc(&in.pinned_in, inb + (size_t)d->max_batch * 4, hipHostMallocDefault) == hipSuccess &&
                   hipHostMalloc(&in.pinned_out, outb, hipHostMallocDefault) == hipSuccess &&
+                  hipHostGetDevicePointer(&in.pinned_in_dev, in.pinned_in, 0) == hipSuccess &&
                   hipHostGetDevicePointer(&in.pinned_out_dev, in.pinned_out, 0) == hipSuccess &&
                   hipMalloc(&in.dev_in, inb) == hipSuccess && hipMalloc(&in.dev_out, outb) == hipSuccess &&
                   hipMalloc((void**)&in.dev_valid, (size_t)d->max_batch * 4 + 256) == hipSuccess &&
@@ -311,6 +312,9 @@ static size_t compute_index(const Context* c, int prio, unsigned n) {
 
 // Stage the input in the instance's pinned buffer (no lock: this is the slow part and instances are
 // independent), then enqueue event / copy / event on copy stream `ci` as one uninterrupted group.
+// Largest input that is copied in by a kernel; above it the copy engines' bandwidth matters more than the rare stall.
+static constexpr size_t KERNEL_H2D_MAX_BYTES = 8u << 20;
+
 static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* host_in, const int32_t* valid_len, size_t ci) {
     Context* c = m->ctx;
     hipStream_t cs = c->copy[ci];
@@ -324,8 +328,15 @@ static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* hos
     }
     std::lock_guard<std::mutex> lk(c->copy_mu[ci]);
     HIP_TRY(hipEventRecord(in.ev_h2d0, cs));
-    HIP_TRY(hipMemcpyAsync(in.dev_in, in.pinned_in, inb, hipMemcpyHostToDevice, cs));
-    if (pv) HIP_TRY(hipMemcpyAsync(in.dev_valid, pv, (size_t)batch * 4, hipMemcpyHostToDevice, cs));
+    if (inb <= KERNEL_H2D_MAX_BYTES && (inb & 3) == 0) {
+        // inputs of serving-sized batches go in by a kernel that reads the pinned buffer over the host link: an
+        // asynchronous copy call of this size now and then blocks its caller for milliseconds
+        if (launch_copy_mapped(in.pinned_in_dev, in.dev_in, inb, 0, cs)) return STRAIT_E_HIP;
+        if (pv && launch_copy_mapped((const char*)in.pinned_in_dev + ((const char*)pv - (const char*)in.pinned_in), in.dev_valid, (size_t)batch * 4, 0, cs)) return STRAIT_E_HIP;
+    } else {
+        HIP_TRY(hipMemcpyAsync(in.dev_in, in.pinned_in, inb, hipMemcpyHostToDevice, cs));
+        if (pv) HIP_TRY(hipMemcpyAsync(in.dev_valid, pv, (size_t)batch * 4, hipMemcpyHostToDevice, cs));
+    }
     HIP_TRY(hipEventRecord(in.ev_h2d1, cs));
     return 0;
 }
@@ -380,7 +391,7 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
         if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
         if (!rc) rc = run_batch(*m, in, batch, s, hp_flag(c, prio));
         if (!rc) rc = hipEventRecord(in.ev_k1, s) == hipSuccess ? 0 : STRAIT_E_HIP;
-        if (!rc) rc = launch_copy_out(in.dev_out, in.pinned_out_dev, m->out_bytes(batch), hp_flag(c, prio), s);
+        if (!rc) rc = launch_copy_mapped(in.dev_out, in.pinned_out_dev, m->out_bytes(batch), hp_flag(c, prio), s);
         if (!rc) rc = hipEventRecord(in.ev_done, s) == hipSuccess ? 0 : STRAIT_E_HIP;
         if (!rc) {
             t->rec.t_issued_ns = now_ns();

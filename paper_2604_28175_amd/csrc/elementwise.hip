@@ -45,27 +45,33 @@ int launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Result hand-over: device buffer -> pinned host memory that the GPU can address, written by a kernel.
-// (A device-to-host hipMemcpyAsync of these few kilobytes sometimes blocks the submitting thread for
-// milliseconds when other streams are busy; a kernel launch does not.)  Both pointers 16-byte aligned,
-// bytes a multiple of 4.
-__global__ void __launch_bounds__(256) copy_out_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, size_t n4, int hp) {
+// Small transfers between pinned host memory that the GPU can address and device memory, done by a kernel:
+// results on their way out, and inputs of up to a few megabytes on their way in.  (A hipMemcpyAsync of such a
+// size, in either direction, now and then blocks the submitting thread for milliseconds when other streams are
+// busy; a kernel launch does not.)  Both pointers 16-byte aligned, bytes a multiple of 4.  Four independent
+// 16-byte loads per thread and round keep enough requests in flight to fill the host link on the way in.
+__global__ void __launch_bounds__(256) copy_mapped_kernel(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, size_t n4, int hp) {
     if (hp) __builtin_amdgcn_s_setprio(3);
     const size_t n16 = n4 >> 2;
     const size_t step = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += step) ((uint4*)dst)[i] = ((const uint4*)src)[i];
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * step < n16; i += 4 * step) {
+        const uint4 a = ((const uint4*)src)[i], b = ((const uint4*)src)[i + step], c = ((const uint4*)src)[i + 2 * step], d = ((const uint4*)src)[i + 3 * step];
+        ((uint4*)dst)[i] = a; ((uint4*)dst)[i + step] = b; ((uint4*)dst)[i + 2 * step] = c; ((uint4*)dst)[i + 3 * step] = d;
+    }
+    for (; i < n16; i += step) ((uint4*)dst)[i] = ((const uint4*)src)[i];
     const size_t tail = n16 << 2;
     if (blockIdx.x == 0 && tail + threadIdx.x < n4) dst[tail + threadIdx.x] = src[tail + threadIdx.x];
 }
-int launch_copy_out(const void* src, void* dst_host_mapped, size_t bytes, int hp, hipStream_t stream) {
+int launch_copy_mapped(const void* src, void* dst, size_t bytes, int hp, hipStream_t stream) {
     if (bytes == 0) return 0;
-    if (!src || !dst_host_mapped || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst_host_mapped) & 15) || (bytes & 3)) {
-        set_error("copy out: 16-byte aligned buffers and a multiple of 4 bytes required"); return -1;
+    if (!src || !dst || (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15) || (bytes & 3)) {
+        set_error("mapped copy: 16-byte aligned buffers and a multiple of 4 bytes required"); return -1;
     }
     const size_t n4 = bytes / 4, n16 = n4 / 4;
     const unsigned blocks = (unsigned)std::min<size_t>(256, std::max<size_t>(1, (n16 + 255) / 256));
-    hipLaunchKernelGGL(copy_out_kernel, dim3(blocks), dim3(256), 0, stream, (const uint32_t*)src, (uint32_t*)dst_host_mapped, n4, hp);
-    STRAIT_CHECK_LAUNCH("copy out");
+    hipLaunchKernelGGL(copy_mapped_kernel, dim3(blocks), dim3(256), 0, stream, (const uint32_t*)src, (uint32_t*)dst, n4, hp);
+    STRAIT_CHECK_LAUNCH("mapped copy");
     return 0;
 }
 

@@ -71,7 +71,7 @@ int launch_argmax_f16(const half_t* x, int rows, int n, long long row_stride, in
 // Weight preparation on the device (load time): BatchNorm fold + OIHW -> kernel layout.
 int launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 // Copies `bytes` (multiple of 4) from device memory to host memory the GPU can address, with a kernel.
-int launch_copy_out(const void* src, void* dst_host_mapped, size_t bytes, int hp, hipStream_t stream);
+int launch_copy_mapped(const void* src, void* dst, size_t bytes, int hp, hipStream_t stream);
 
 void set_error(const char* fmt, ...);
 

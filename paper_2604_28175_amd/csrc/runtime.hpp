@@ -59,6 +59,7 @@ struct Op {
 
 struct Instance {
     void* pinned_in = nullptr;
+    void* pinned_in_dev = nullptr;     // the same memory as the GPU addresses it
     void* pinned_out = nullptr;
     void* pinned_out_dev = nullptr;    // the same memory as the GPU addresses it
     void* dev_in = nullptr;
