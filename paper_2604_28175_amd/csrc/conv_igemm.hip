@@ -653,6 +653,250 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(const ConvParams p) 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// 3x3, stride 1, padding 1, from an input patch held in LDS.
+//
+// The kernel above fetches every input pixel nine times, once per filter tap; on the wide early layers that
+// traffic between L2 and LDS, not the MFMAs, sets the pace.  Here output pixels are numbered in the image with
+// its zero border, v = (n (H+2) + y) (W+2) + x, so that tap (r, s) of output v reads bordered input pixel
+// v + r (W+2) + s: one offset per tap for the whole tile.  A workgroup owns BM consecutive v (those with
+// y >= H or x >= W are computed and never stored) and BN output channels.  Per 32-channel slice of the input it
+// holds the BM + 2 (W+2) + 2 bordered pixels its taps touch (64 bytes each; border pixels arrive as zeros from
+// out-of-range transfers) and feeds all nine taps' MFMAs from them; only the weights, one 32-channel slice of
+// one tap at a time, stream through a three-stage ring.  The patch of the next slice arrives in a second buffer
+// during the first seven tap steps of the current one.  Per tap step every wave issues a fixed number of
+// transfers, so the in-order load counter tells when a given stage has landed.  LDS rows of 64 bytes are
+// swizzled as in the kernel above (16-byte chunk c of row i sits at c ^ ((i >> 2) & 3)), which keeps the
+// operand reads conflict free for any run of consecutive rows, i.e. for every tap offset.
+__device__ __forceinline__ void divmod_f(int v, int d, float rcp, int& q, int& r) {   // exact for 0 <= v < 2^24
+    q = (int)((float)v * rcp);
+    r = v - q * d;
+    if (r < 0) { --q; r += d; }
+    if (r >= d) { ++q; r -= d; }
+}
+constexpr int patch_share(int npw, int as, int t) { return npw - t * as < 0 ? 0 : (npw - t * as > as ? as : npw - t * as); }
+
+template <int BM, int BN, int WGM, int WGN, int NPW>
+__global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_kernel(const ConvParams p) {
+    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    static_assert((NW == 4 || NW == 8) && BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0 && BN % (16 * NW) == 0, "unsupported tile");
+    constexpr int TM = BM / WGM, TN = BN / WGN, TMB = TM / 32, TNB = TN / 32;
+    constexpr int WI = BN / (NW * 16);                 // weight transfers per wave per tap step
+    constexpr int AS = (NPW + 6) / 7;                  // patch transfers per wave per tap step (steps 0..6)
+    constexpr int PATCH = NPW * NW * 1024;             // bytes of one patch buffer: NPW * 64 pixels
+    constexpr int WSTAGE = BN * 64;                    // bytes of one weight stage
+    constexpr int RING = 2 * PATCH + 3 * WSTAGE;
+    constexpr int LDC = BN + 8;
+    constexpr int CT = BM * LDC * 2;
+    constexpr unsigned BIAS_LDS = RING > CT ? RING : CT;
+    static_assert(BIAS_LDS + 1024 <= 160 * 1024, "LDS limit");
+
+    extern __shared__ __attribute__((aligned(1024))) half_t smem[];
+    const unsigned lds0 = (unsigned)(uintptr_t)smem;
+    if (p.hp) __builtin_amdgcn_s_setprio(3);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave % WGM) * TM, wn0 = (wave / WGM) * TN;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    const int tiles_n = p.Cout / BN;
+    int tile;
+    {
+        const int nb = gridDim.x, b = blockIdx.x;
+        const int per = nb >> 3, rem = nb & 7, xcd = b & 7, idx = b >> 3;
+        tile = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
+    const int tm = tile / tiles_n;
+    const int m0 = tm * BM, n0 = (tile - tm * tiles_n) * BN;
+
+    // rows wider than 128 pixels are cut into strips, each numbered as an image of its own whose left and right
+    // "border" columns are the neighbouring strips' pixels (zeros only at the true edges)
+    const int SW = p.strip_w, NS = p.W / SW;
+    const int Wp = SW + 2, HpWp = (p.H + 2) * Wp, NI = (p.M / p.PQ) * NS;
+    const float rcp_w = 1.f / (float)Wp, rcp_i = 1.f / (float)HpWp, rcp_s = 1.f / (float)NS;
+    const intx4 xrsrc = make_rsrc(p.x, (unsigned)(p.x_elems * 2));
+    const intx4 wrsrc = make_rsrc(p.w, (unsigned)((long long)p.Cout * p.ldw * 2));
+
+    // ---- per-lane source offsets: patch pixel (16 per transfer, 4 chunks each), weight row ----------
+    unsigned aoff[NPW];
+#pragma unroll
+    for (int j = 0; j < NPW; ++j) {
+        const int pp = (j * NW + wave) * 16 + (lane >> 2);
+        int img, rem, yp, xp, n, st;
+        divmod_f(m0 + pp, HpWp, rcp_i, img, rem);
+        divmod_f(rem, Wp, rcp_w, yp, xp);
+        divmod_f(img, NS, rcp_s, n, st);
+        const int xr = st * SW + xp - 1;
+        const int lc = (lane & 3) ^ ((pp >> 2) & 3);
+        const bool inside = img < NI && yp >= 1 && yp <= p.H && xr >= 0 && xr < p.W;
+        aoff[j] = inside ? (unsigned)(((long long)n * p.sN + (long long)(yp - 1) * p.sH + (long long)xr * p.sW + lc * 8) * 2) : OOB_OFFSET;
+    }
+    unsigned woff[WI];
+#pragma unroll
+    for (int j = 0; j < WI; ++j) {
+        const int row = (j * NW + wave) * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((row >> 2) & 3);
+        woff[j] = n0 + row < p.Cout ? (unsigned)(((long long)(n0 + row) * p.ldw + lc * 8) * 2) : OOB_OFFSET;
+    }
+    const int ncs = p.C >> 5;
+    auto issue_w = [&](int stage, int tap, int cs) {
+        const bool live = cs < ncs;
+        const unsigned soff = live ? (unsigned)(tap * p.C + cs * 32) * 2u : 0u;
+#pragma unroll
+        for (int j = 0; j < WI; ++j)
+            dma16(wrsrc, live ? woff[j] : OOB_OFFSET, soff, lds0 + (unsigned)(2 * PATCH + stage * WSTAGE + (j * NW + wave) * 1024));
+    };
+    auto issue_a = [&](int buf, int j, int cs) {
+        const bool live = cs < ncs;
+        dma16(xrsrc, live ? aoff[j] : OOB_OFFSET, live ? (unsigned)cs * 64u : 0u, lds0 + (unsigned)(buf * PATCH + (j * NW + wave) * 1024));
+    };
+
+    floatx16 acc[TNB][TMB];
+#pragma unroll
+    for (int a = 0; a < TNB; ++a)
+#pragma unroll
+        for (int b = 0; b < TMB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    static_assert(BN <= 256, "bias row: one transfer carries 256 floats");
+    if (wave == 0) {
+        const intx4 brsrc = make_rsrc(p.bias, p.bias ? (unsigned)p.Cout * 4u : 0u);
+        const int c = n0 + lane * 4;
+        dma16(brsrc, (p.bias && lane * 4 < BN && c + 3 < p.Cout) ? (unsigned)c * 4u : OOB_OFFSET, 0u, lds0 + BIAS_LDS);
+    }
+#pragma unroll
+    for (int j = 0; j < NPW; ++j) issue_a(0, j, 0);
+    issue_w(0, 0, 0);
+    issue_w(1, 1, 0);
+
+    const unsigned wrow = (unsigned)((lh ^ ((l32 >> 2) & 3)) << 4);   // chunk lh of weight row l32 (+ multiples of 32 rows)
+    for (int cs = 0; cs < ncs; ++cs) {
+        const char* Pa = (const char*)smem + (cs & 1) * PATCH;
+        const int nbuf = (cs + 1) & 1;
+        int wp_l = Wp;                                 // opaque per iteration: keeps the nine taps' operand addresses from being
+        asm volatile("" : "+s"(wp_l));                 // hoisted out of the loop, where they would cost eighteen registers
+#define STRAIT_TAP_STEP(T)                                                                                              \
+        {                                                                                                               \
+            wait_loads_then_barrier<patch_share(NPW, AS, (T + 7) % 9) + WI + patch_share(NPW, AS, (T + 8) % 9)>();      \
+            const char* Ws = (const char*)smem + 2 * PATCH + (T % 3) * WSTAGE;                                          \
+            const int tapoff = (T / 3) * wp_l + (T % 3);                                                                 \
+            unsigned a0[TMB];                                                                                           \
+            _Pragma("unroll") for (int b = 0; b < TMB; ++b) {                                                           \
+                const unsigned pp = (unsigned)(wm0 + b * 32 + l32 + tapoff);                                            \
+                a0[b] = pp * 64u + (((lh ^ (pp >> 2)) & 3u) << 4);                                                      \
+            }                                                                                                           \
+            half8 wf[2][TNB], xf[2][TMB];                                                                               \
+            _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[0][a] = *(const half8*)(Ws + (wn0 + a * 32 + l32) * 64 + wrow); \
+            _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[0][b] = *(const half8*)(Pa + a0[b]);                     \
+            issue_w((T + 2) % 3, (T + 2) % 9, cs + (T + 2) / 9);                                                        \
+            _Pragma("unroll") for (int j = T * AS; j < (T + 1) * AS && j < NPW; ++j) issue_a(nbuf, j, cs + 1);          \
+            _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[1][a] = *(const half8*)(Ws + (((wn0 + a * 32 + l32) * 64 + wrow) ^ 32u)); \
+            _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[1][b] = *(const half8*)(Pa + (a0[b] ^ 32u));             \
+            __builtin_amdgcn_sched_barrier(0);                                                                          \
+            _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                            \
+                _Pragma("unroll") for (int a = 0; a < TNB; ++a)                                                         \
+                    _Pragma("unroll") for (int b = 0; b < TMB; ++b)                                                     \
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[ks][a], xf[ks][b], acc[a][b], 0, 0, 0);   \
+            __builtin_amdgcn_sched_barrier(0);                                                                          \
+        }
+        STRAIT_TAP_STEP(0) STRAIT_TAP_STEP(1) STRAIT_TAP_STEP(2) STRAIT_TAP_STEP(3) STRAIT_TAP_STEP(4)
+        STRAIT_TAP_STEP(5) STRAIT_TAP_STEP(6) STRAIT_TAP_STEP(7) STRAIT_TAP_STEP(8)
+#undef STRAIT_TAP_STEP
+    }
+    wait_loads_then_barrier<0>();                      // trailing (empty) transfers have landed; LDS is free
+
+    // ---- epilogue: bias, clamp, tile parked in LDS as [pixel][channel], 16-byte row segments out ----
+    half_t* Cs = smem;
+    const half_t lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? (half_t)0.f : (half_t)-INFINITY;
+    const half_t hi = p.act == ACT_RELU6 ? (half_t)6.f : (half_t)INFINITY;
+    const half4 lo4 = {lo, lo, lo, lo}, hi4 = {hi, hi, hi, hi};
+    const float* bias_s = (const float*)((const char*)smem + BIAS_LDS);
+#pragma unroll
+    for (int a = 0; a < TNB; ++a)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int cn = wn0 + a * 32 + 8 * g + 4 * lh;
+            const float4 b4 = *(const float4*)(bias_s + cn);
+            const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+            for (int b = 0; b < TMB; ++b) {
+                half4 h;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = (half_t)(acc[a][b][4 * g + j] + bv[j]);
+                h = __builtin_elementwise_min(__builtin_elementwise_max(h, lo4), hi4);
+                *(half4*)(Cs + (wm0 + b * 32 + l32) * LDC + cn) = h;
+            }
+        }
+    __syncthreads();
+    constexpr int CPR = BN / 8, NCH = BM * CPR / NT;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int id = tid + i * NT;
+        const int row = id / CPR, c8 = id - row * CPR;
+        int img, rem, yy, xx, n, st;
+        divmod_f(m0 + row, HpWp, rcp_i, img, rem);
+        divmod_f(rem, Wp, rcp_w, yy, xx);
+        divmod_f(img, NS, rcp_s, n, st);
+        if (img < NI && yy < p.H && xx < SW) {
+            const half8 v = *(const half8*)(Cs + row * LDC + c8 * 8);
+            *(half8*)((half_t*)p.y + ((long long)(n * p.H + yy) * p.W + st * SW + xx) * p.ldy + n0 + c8 * 8) = v;
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int NPW>
+static int launch_patch_tile(const ConvParams& p, long long mv, hipStream_t stream) {
+    constexpr int NW = WGM * WGN;
+    const long long tiles = ((mv + BM - 1) / BM) * (p.Cout / BN);
+    if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
+    constexpr unsigned ring = 2 * NPW * NW * 1024 + 3 * BN * 64, ctile = BM * (BN + 8) * 2;
+    constexpr unsigned lds = (ring > ctile ? ring : ctile) + 1024;
+    auto kernel = conv3x3_patch_kernel<BM, BN, WGM, WGN, NPW>;
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire) && lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
+    }
+    configured.store(true, std::memory_order_release);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(64 * NW), lds, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
+    return 0;
+}
+
+// Whether the patch kernel takes a layer, and with which tile; -1 = not this kernel's.
+static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
+    ConvParams p = params;
+    int sw = p.W;
+    while (sw > 64 && sw % 2 == 0) sw /= 2;
+    if (sw > 128) return -1;
+    p.strip_w = sw;
+    const int wp = sw + 2;
+    const long long mv = (long long)(p.M / p.PQ) * (p.W / sw) * (p.H + 2) * wp;
+    if (mv >= (1LL << 24) - 4096) return -1;           // the kernel's index arithmetic is exact below 2^24
+    auto per_wave = [&](int bm, int nw) { return ((bm + 2 * wp + 2 + 15) / 16 + nw - 1) / nw; };
+    if (p.Cout % 128 == 0) {
+        if (((mv + 255) / 256) * (p.Cout / 128) >= 768) {          // a round and a half of workgroups at least: 8 waves on 256 x 128
+            const int npw = per_wave(256, 8);
+            if (npw <= 3) return launch_patch_tile<256, 128, 4, 2, 3>(p, mv, stream);
+            if (npw <= 4) return launch_patch_tile<256, 128, 4, 2, 4>(p, mv, stream);
+        }
+        const int npw = per_wave(128, 4);
+        if (npw <= 4) return launch_patch_tile<128, 128, 2, 2, 4>(p, mv, stream);
+        if (npw <= 6) return launch_patch_tile<128, 128, 2, 2, 6>(p, mv, stream);
+        return -1;
+    }
+    if (p.Cout % 64 == 0) {
+        const int npw = per_wave(256, 4);
+        if (npw <= 6) return launch_patch_tile<256, 64, 4, 1, 6>(p, mv, stream);
+        if (npw <= 8) return launch_patch_tile<256, 64, 4, 1, 8>(p, mv, stream);
+        return -1;
+    }
+    return -1;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN) * p.ksplit;
@@ -742,7 +986,11 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         const long long t = tiles(64, 64);
         const int nk = (p.Kg + 31) / 32;
         if (t <= 128 && nk >= 8) {
-            long long ks = (320 + t - 1) / t;
+            // about one workgroup per CU and a bit hides the chain of slices; a layer that streams megabytes of
+            // weights for a handful of rows (the fully connected layers of a plain CNN) is bound by the bytes in
+            // flight and takes four times as many
+            const long long target = (long long)p.Cout * p.Kg * 2 >= (8LL << 20) ? 1280 : 320;
+            long long ks = (target + t - 1) / t;
             if (ks > nk / 4) ks = nk / 4;
             if (ks > 32) ks = 32;
             while (ks > 1 && ks * (long long)p.M * p.Cout * 4 > (long long)p.ws_bytes) --ks;
@@ -751,6 +999,12 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
                 return launch_dma_tile<64, 64, 32, 2, 2, 3>(p, mode, stream);
             }
         }
+    }
+    // wide 3x3 stride-1 layers: the patch kernel fetches each input pixel once per slice instead of once per tap
+    if (staged && regular && small && mode == MODE_GATHER8 && p.R == 3 && p.S == 3 && p.stride_h == 1 && p.stride_w == 1 &&
+        p.pad_h == 1 && p.pad_w == 1 && !p.res && p.act != ACT_GELU && p.W >= 28 && p.Q == p.W && p.PQ == p.H * p.W && p.ldy % 8 == 0) {
+        const int rc = launch_conv3x3_patch(p, stream);
+        if (rc != -1) return rc;
     }
     if (staged && regular && small) {
         // Tile choice, from sweeps over the served networks' layer shapes on MI355X:

@@ -41,6 +41,7 @@ struct ConvParams {
     size_t ws_bytes;
     int ksplit;              // filled in by launch_conv
     int tiles_n_shift;       // log2 of the number of tiles along Cout, or -1; filled in by the launcher
+    int strip_w;             // 3x3 patch kernel: width of the strips a row is cut into; filled in by the launcher
 };
 
 int launch_conv(const ConvParams& p, hipStream_t stream);

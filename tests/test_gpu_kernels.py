@@ -48,6 +48,12 @@ CONV_CASES = [
     (1, 40, 40, 64, 64, 3, 1, 1, 1, False, False),      # several 128-pixel tiles and a ragged tail (M = 1600)
     (1, 7, 7, 512, 512, 3, 1, 1, 1, False, False),      # long reduction (K = 4608), small M
     (11, 56, 56, 64, 256, 1, 1, 0, 1, True, False),     # 64 -> 256 pointwise with residual, M = 34496: many tiles, ragged tail, residual requested early
+    # wide 3x3 stride-1 layers with enough output tiles not to split the reduction: the kernel that keeps an input patch in LDS
+    (3, 56, 56, 64, 64, 3, 1, 1, 1, False, False),      # 64 channels out: 256-pixel tiles, two input slices
+    (6, 28, 28, 32, 128, 3, 1, 1, 1, False, False),     # 128 channels out: 128-pixel tiles, a single input slice, smallest patch
+    (1, 37, 112, 64, 128, 3, 1, 1, 0, False, False),    # wider rows (larger patch), ragged height, no activation
+    (2, 24, 224, 32, 64, 3, 1, 1, 1, False, False),     # widest rows served: the largest patch
+    (2, 40, 100, 96, 192, 3, 1, 1, 2, False, False),    # three channel tiles, three input slices, ReLU6
 ]
 
 
