@@ -337,7 +337,7 @@ def main() -> int:
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic(B),
                      "algorithmic_bytes_per_step": sum(float(layers[i].bytes_per_sample) * B + layers[i].weight_bytes for i in conv),
-                     "kernel": "conv_igemm_dma_kernel (all tile shapes) and stem_pool_kernel: the 54 MFMA launches of a step (53 convolutions, the first fused with the pooling behind it, and the classifier)",
+                     "kernel": "conv_igemm_dma_kernel (all tile shapes), conv3x3_patch_kernel and stem_pool_kernel: the 54 MFMA launches of a step (53 convolutions, the first fused with the pooling behind it, and the classifier)",
                      "flops_per_step": conv_flops, "kernel_ms_per_step": round(conv_ms, 4),
                      "other_kernels_ms_per_step": round(other_ms, 4),
                      "layerwise_roofline_ms": round(t_roof * 1e3, 4),

@@ -676,16 +676,24 @@ __device__ __forceinline__ void divmod_f(int v, int d, float rcp, int& q, int& r
 }
 constexpr int patch_share(int npw, int as, int t) { return npw - t * as < 0 ? 0 : (npw - t * as > as ? as : npw - t * as); }
 
-template <int BM, int BN, int WGM, int WGN, int NPW>
+constexpr int patch_wait(int npw, int as, int wi, int pre, int t) {     // transfers a wave may have in flight when tap step t starts
+    int n = patch_share(npw, as, (t + 9 - pre) % 9);
+    for (int k = 1; k < pre; ++k) n += wi + patch_share(npw, as, (t + 9 - k) % 9);
+    return n;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
 __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_kernel(const ConvParams p) {
     constexpr int NW = WGM * WGN, NT = 64 * NW;
     static_assert((NW == 4 || NW == 8) && BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0 && BN % (16 * NW) == 0, "unsupported tile");
     constexpr int TM = BM / WGM, TN = BN / WGN, TMB = TM / 32, TNB = TN / 32;
     constexpr int WI = BN / (NW * 16);                 // weight transfers per wave per tap step
-    constexpr int AS = (NPW + 6) / 7;                  // patch transfers per wave per tap step (steps 0..6)
+    constexpr int PRE = NBS - 1;                       // weight stages in flight ahead of the one in use
+    constexpr int AS = (NPW + 8 - PRE) / (9 - PRE);    // patch transfers per wave per tap step (steps 0..8-PRE)
+    static_assert(NBS >= 3 && NBS <= 8, "ring depth");
     constexpr int PATCH = NPW * NW * 1024;             // bytes of one patch buffer: NPW * 64 pixels
     constexpr int WSTAGE = BN * 64;                    // bytes of one weight stage
-    constexpr int RING = 2 * PATCH + 3 * WSTAGE;
+    constexpr int RING = 2 * PATCH + NBS * WSTAGE;
     constexpr int LDC = BN + 8;
     constexpr int CT = BM * LDC * 2;
     constexpr unsigned BIAS_LDS = RING > CT ? RING : CT;
@@ -768,8 +776,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
     }
 #pragma unroll
     for (int j = 0; j < NPW; ++j) issue_a(0, j, 0);
-    issue_w(0, 0, 0);
-    issue_w(1, 1, 0);
+#pragma unroll
+    for (int t = 0; t < PRE; ++t) issue_w(t, t, 0);    // PRE < 9: all in the first slice
+    int rd = 0, wr = PRE;                              // ring stage in use, stage being filled
 
     const unsigned wrow = (unsigned)((lh ^ ((l32 >> 2) & 3)) << 4);   // chunk lh of weight row l32 (+ multiples of 32 rows)
     for (int cs = 0; cs < ncs; ++cs) {
@@ -779,8 +788,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
         asm volatile("" : "+s"(wp_l));                 // hoisted out of the loop, where they would cost eighteen registers
 #define STRAIT_TAP_STEP(T)                                                                                              \
         {                                                                                                               \
-            wait_loads_then_barrier<patch_share(NPW, AS, (T + 7) % 9) + WI + patch_share(NPW, AS, (T + 8) % 9)>();      \
-            const char* Ws = (const char*)smem + 2 * PATCH + (T % 3) * WSTAGE;                                          \
+            wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T)>();                                                  \
+            const char* Ws = (const char*)smem + 2 * PATCH + rd * WSTAGE;                                               \
             const int tapoff = (T / 3) * wp_l + (T % 3);                                                                 \
             unsigned a0[TMB];                                                                                           \
             _Pragma("unroll") for (int b = 0; b < TMB; ++b) {                                                           \
@@ -790,7 +799,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
             half8 wf[2][TNB], xf[2][TMB];                                                                               \
             _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[0][a] = *(const half8*)(Ws + (wn0 + a * 32 + l32) * 64 + wrow); \
             _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[0][b] = *(const half8*)(Pa + a0[b]);                     \
-            issue_w((T + 2) % 3, (T + 2) % 9, cs + (T + 2) / 9);                                                        \
+            issue_w(wr, (T + PRE) % 9, cs + (T + PRE) / 9);                                                             \
+            rd = rd + 1 == NBS ? 0 : rd + 1;                                                                            \
+            wr = wr + 1 == NBS ? 0 : wr + 1;                                                                            \
             _Pragma("unroll") for (int j = T * AS; j < (T + 1) * AS && j < NPW; ++j) issue_a(nbuf, j, cs + 1);          \
             _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[1][a] = *(const half8*)(Ws + (((wn0 + a * 32 + l32) * 64 + wrow) ^ 32u)); \
             _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[1][b] = *(const half8*)(Pa + (a0[b] ^ 32u));             \
@@ -846,14 +857,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int NPW>
+template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
 static int launch_patch_tile(const ConvParams& p, long long mv, hipStream_t stream) {
     constexpr int NW = WGM * WGN;
     const long long tiles = ((mv + BM - 1) / BM) * (p.Cout / BN);
     if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
-    constexpr unsigned ring = 2 * NPW * NW * 1024 + 3 * BN * 64, ctile = BM * (BN + 8) * 2;
+    constexpr unsigned ring = 2 * NPW * NW * 1024 + NBS * BN * 64, ctile = BM * (BN + 8) * 2;
     constexpr unsigned lds = (ring > ctile ? ring : ctile) + 1024;
-    auto kernel = conv3x3_patch_kernel<BM, BN, WGM, WGN, NPW>;
+    auto kernel = conv3x3_patch_kernel<BM, BN, WGM, WGN, NPW, NBS>;
     static std::atomic<bool> configured{false};
     if (!configured.load(std::memory_order_acquire) && lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -880,18 +891,18 @@ static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
     if (p.Cout % 128 == 0) {
         if (((mv + 255) / 256) * (p.Cout / 128) >= 768) {          // a round and a half of workgroups at least: 8 waves on 256 x 128
             const int npw = per_wave(256, 8);
-            if (npw <= 3) return launch_patch_tile<256, 128, 4, 2, 3>(p, mv, stream);
-            if (npw <= 4) return launch_patch_tile<256, 128, 4, 2, 4>(p, mv, stream);
+            if (npw <= 3) return launch_patch_tile<256, 128, 4, 2, 3, 3>(p, mv, stream);
+            if (npw <= 4) return launch_patch_tile<256, 128, 4, 2, 4, 3>(p, mv, stream);
         }
         const int npw = per_wave(128, 4);
-        if (npw <= 4) return launch_patch_tile<128, 128, 2, 2, 4>(p, mv, stream);
-        if (npw <= 6) return launch_patch_tile<128, 128, 2, 2, 6>(p, mv, stream);
+        if (npw <= 4) return launch_patch_tile<128, 128, 2, 2, 4, 3>(p, mv, stream);
+        if (npw <= 6) return launch_patch_tile<128, 128, 2, 2, 6, 3>(p, mv, stream);
         return -1;
     }
     if (p.Cout % 64 == 0) {
         const int npw = per_wave(256, 4);
-        if (npw <= 6) return launch_patch_tile<256, 64, 4, 1, 6>(p, mv, stream);
-        if (npw <= 8) return launch_patch_tile<256, 64, 4, 1, 8>(p, mv, stream);
+        if (npw <= 6) return launch_patch_tile<256, 64, 4, 1, 6, 3>(p, mv, stream);
+        if (npw <= 8) return launch_patch_tile<256, 64, 4, 1, 8, 3>(p, mv, stream);
         return -1;
     }
     return -1;
