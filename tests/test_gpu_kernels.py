@@ -86,6 +86,21 @@ def test_conv2d_integer_data_is_bit_exact(S):
         assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref)
 
 
+@pytest.mark.parametrize("N,H,W,C,K", [(4, 40, 60, 32, 64),      # 256-pixel tiles, one strip per row
+                                       (2, 36, 128, 32, 128),    # rows cut into two strips of 64: the strips' side borders are real pixels
+                                       (1, 29, 224, 64, 64)])    # four strips of 56, two input slices
+def test_conv2d_wide_3x3_integer_data_is_bit_exact(S, N, H, W, C, K):
+    """The wide 3x3 stride-1 layers run from an input patch in LDS, addressed through the bordered image: with
+    integer data every border, strip seam and tile seam must come out exactly."""
+    x = R.integers(-3, 4, (N, H, W, C)).astype(np.float16)
+    w = R.integers(-2, 3, (K, C, 3, 3)).astype(np.float16)
+    b = R.integers(-5, 6, K).astype(np.float32)
+    ref = ops.conv2d(x, w, b, 1, 1)
+    assert np.abs(ref).max() < 2048
+    y = S.k_conv2d(dev(S, x), dev(S, np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))), dev(S, b), 1, 1)
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref)
+
+
 def test_conv2d_tap_count_pattern(S):
     y = S.k_conv2d(dev(S, np.ones((1, 6, 6, 8), np.float16)), dev(S, np.ones((8, 3, 3, 8), np.float16)), None, 2, 1)
     got = y.float().cpu().numpy()[0, :, :, 0] / 8
