@@ -285,6 +285,80 @@ __global__ void __launch_bounds__(256) dwconv3x3_s1_2rows_kernel(const half_t* _
     }
 }
 
+// Stride 1, a column of TH outputs per thread.  Consecutive threads own consecutive 16-byte chunks along an image
+// row (pixel-major, then channel group), so every load and store instruction of a wavefront covers one contiguous
+// kilobyte whatever the channel count; a thread fetches the left, centre and right vector of each of the TH + 2
+// input rows its column touches (the neighbours' copies of the same vectors hit in L1).  The strips of the kernels
+// above leave, with few channels, gaps of TW pixels between the lanes of one instruction.  Every output
+// accumulates its nine taps in the same order as there, so results are identical.
+template <int TH>
+__global__ void __launch_bounds__(256) dwconv3x3_s1_cols_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
+                                                                 const half_t* __restrict__ w, const float* __restrict__ bias,
+                                                                 int act, half_t* __restrict__ y, int hp) {
+    if (hp) __builtin_amdgcn_s_setprio(3);
+    const unsigned C8 = (unsigned)C >> 3;
+    const unsigned PT = (unsigned)(H + TH - 1) / TH;
+    const unsigned long long total = (unsigned long long)N * PT * W * C8;
+    const unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const unsigned c8 = (unsigned)(i % C8);
+    unsigned t = (unsigned)(i / C8);
+    const unsigned q = t % (unsigned)W; t /= (unsigned)W;
+    const unsigned pt = t % PT;
+    const unsigned n = t / PT;
+    const int c = (int)c8 * 8;
+    half8 wv[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) wv[k] = *(const half8*)(w + (long long)k * C + c);
+    float acc[TH][8];
+    {
+        float bv[8];
+        if (bias) {
+            const float4 b0 = *(const float4*)(bias + c), b1 = *(const float4*)(bias + c + 4);
+            bv[0] = b0.x; bv[1] = b0.y; bv[2] = b0.z; bv[3] = b0.w; bv[4] = b1.x; bv[5] = b1.y; bv[6] = b1.z; bv[7] = b1.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) bv[j] = 0.f;
+        }
+#pragma unroll
+        for (int o = 0; o < TH; ++o)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[o][j] = bv[j];
+    }
+    const int p0 = (int)pt * TH;
+    const half_t* xin = x + ((long long)n * H * W + q) * C + c;
+    const bool has_l = q > 0, has_r = q + 1 < (unsigned)W;
+#pragma unroll
+    for (int r = 0; r < TH + 2; ++r) {
+        const int ih = p0 - 1 + r;
+        if ((unsigned)ih >= (unsigned)H) continue;
+        const half_t* row = xin + (long long)ih * W * C;
+        half8 xv[3];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { xv[0][j] = (half_t)0; xv[2][j] = (half_t)0; }
+        if (has_l) xv[0] = *(const half8*)(row - C);
+        xv[1] = *(const half8*)row;
+        if (has_r) xv[2] = *(const half8*)(row + C);
+#pragma unroll
+        for (int o = 0; o < TH; ++o) {
+            const int fr = r - o;                       // filter row this input row is for output row p0 + o
+            if (fr < 0 || fr > 2) continue;
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[o][j] += (float)xv[sx][j] * (float)wv[fr * 3 + sx][j];
+        }
+    }
+#pragma unroll
+    for (int o = 0; o < TH; ++o) {
+        if (p0 + o >= H) continue;
+        half8 ov;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ov[j] = (half_t)act_f(acc[o][j], act);
+        *(half8*)(y + (((long long)n * H + p0 + o) * W + q) * C + c) = ov;
+    }
+}
+
 int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
                      int stride, int act, half_t* y, int hp, hipStream_t stream) {
     if (!x || !w_rsc || !y || N <= 0 || H <= 0 || W <= 0 || C <= 0 || C % 8 != 0 || (stride != 1 && stride != 2)) {
@@ -299,7 +373,11 @@ int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* 
     if (blocks > 0x7fffffffLL || (long long)N * P * ((Q + TW - 1) / TW) > 0xffffffffLL) { set_error("dwconv3x3: grid too large"); return -5; }
     // two output rows per thread save a third of the loads, but halve the threads: only for grids that still fill the chip
     const long long total2 = (long long)N * ((H + 1) / 2) * ((W + TW - 1) / TW) * (C / 8);
-    if (stride == 1 && H >= 2 && total2 >= 120000) {
+    constexpr int TH = 4;
+    const long long total_cols = (long long)N * ((H + TH - 1) / TH) * W * (C / 8);
+    if (stride == 1 && total_cols >= 16384 && (total_cols + 255) / 256 <= 0x7fffffffLL && (long long)N * ((H + TH - 1) / TH) * W <= 0xffffffffLL) {
+        hipLaunchKernelGGL((dwconv3x3_s1_cols_kernel<TH>), dim3((unsigned)((total_cols + 255) / 256)), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, hp);
+    } else if (stride == 1 && H >= 2 && total2 >= 120000) {
         hipLaunchKernelGGL((dwconv3x3_s1_2rows_kernel<TW>), dim3((unsigned)((total2 + 255) / 256)), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, hp);
     } else if (stride == 1)
         hipLaunchKernelGGL((dwconv3x3_kernel<1, TW>), dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, P, Q, hp);

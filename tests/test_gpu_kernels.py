@@ -124,7 +124,9 @@ def test_gemm(S, M, N, K, act, use_res, out_f32):
     check_kernel(y.float().cpu().numpy(), ref, f"gemm {M}x{N}x{K}")
 
 
-@pytest.mark.parametrize("N,H,W,C,stride", [(2, 14, 14, 96, 1), (2, 15, 13, 144, 2), (1, 7, 7, 960, 1), (3, 28, 28, 32, 2), (1, 9, 10, 8, 1)])
+@pytest.mark.parametrize("N,H,W,C,stride", [(2, 14, 14, 96, 1), (2, 15, 13, 144, 2), (1, 7, 7, 960, 1), (3, 28, 28, 32, 2), (1, 9, 10, 8, 1),
+                                            # stride 1 with enough work for the column kernel: few channels, ragged height, many channels
+                                            (6, 56, 56, 32, 1), (5, 30, 27, 144, 1), (16, 7, 7, 960, 1)])
 def test_dwconv3x3(S, N, H, W, C, stride):
     x = f16(R.standard_normal((N, H, W, C)) * 2)
     w = f16(R.standard_normal((C, 1, 3, 3)) * 0.47)
