@@ -199,96 +199,10 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const half_t* __restrict
 }
 
 
-// Stride 1, two output rows per thread: the four input rows a 2 x TW block of outputs touches are loaded
-// once each (4 x (TW + 2) vectors for 2 x TW outputs: 3 loads per output instead of 4.5); every output
-// still accumulates its nine taps in the same order as the one-row kernel, so results are identical.
-template <int TW>
-__global__ void __launch_bounds__(256) dwconv3x3_s1_2rows_kernel(const half_t* __restrict__ x, int N, int H, int W, int C,
-                                                                  const half_t* __restrict__ w, const float* __restrict__ bias,
-                                                                  int act, half_t* __restrict__ y, int hp) {
-    if (hp) __builtin_amdgcn_s_setprio(3);
-    constexpr int NV = TW + 2;
-    const unsigned C8 = (unsigned)C >> 3;
-    const unsigned QT = (unsigned)(W + TW - 1) / TW, PT = (unsigned)(H + 1) / 2;      // P = H, Q = W
-    const unsigned long long total = (unsigned long long)N * PT * QT * C8;
-    const unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const unsigned c8 = (unsigned)(i % C8);
-    unsigned t = (unsigned)(i / C8);
-    const unsigned qt = t % QT; t /= QT;
-    const unsigned pt = t % PT;
-    const unsigned n = t / PT;
-    const int c = (int)c8 * 8;
-    half8 wv[9];
-#pragma unroll
-    for (int k = 0; k < 9; ++k) wv[k] = *(const half8*)(w + (long long)k * C + c);
-    float acc[2][TW][8];
-    {
-        float bv[8];
-        if (bias) {
-            const float4 b0 = *(const float4*)(bias + c), b1 = *(const float4*)(bias + c + 4);
-            bv[0] = b0.x; bv[1] = b0.y; bv[2] = b0.z; bv[3] = b0.w; bv[4] = b1.x; bv[5] = b1.y; bv[6] = b1.z; bv[7] = b1.w;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) bv[j] = 0.f;
-        }
-#pragma unroll
-        for (int o = 0; o < 2; ++o)
-#pragma unroll
-            for (int tq = 0; tq < TW; ++tq)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[o][tq][j] = bv[j];
-    }
-    const int p0 = (int)pt * 2, q0 = (int)qt * TW;
-    const int iw0 = q0 - 1;
-    const half_t* xin = x + (long long)n * H * W * C + c;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int ih = p0 - 1 + r;
-        if ((unsigned)ih >= (unsigned)H) continue;
-        const half_t* row = xin + (long long)ih * W * C;
-        half8 xv[NV];
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const int iw = iw0 + k;
-            if ((unsigned)iw < (unsigned)W) xv[k] = *(const half8*)(row + (long long)iw * C);
-            else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) xv[k][j] = (half_t)0;
-            }
-        }
-#pragma unroll
-        for (int o = 0; o < 2; ++o) {
-            const int fr = r - o;                       // filter row this input row is for output row p0 + o
-            if (fr < 0 || fr > 2) continue;
-#pragma unroll
-            for (int tq = 0; tq < TW; ++tq)
-#pragma unroll
-                for (int sx = 0; sx < 3; ++sx)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[o][tq][j] += (float)xv[tq + sx][j] * (float)wv[fr * 3 + sx][j];
-        }
-    }
-#pragma unroll
-    for (int o = 0; o < 2; ++o) {
-        if (p0 + o >= H) continue;
-        half_t* yout = y + (((long long)n * H + p0 + o) * W + q0) * C + c;
-#pragma unroll
-        for (int tq = 0; tq < TW; ++tq) {
-            if (q0 + tq < W) {
-                half8 ov;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) ov[j] = (half_t)act_f(acc[o][tq][j], act);
-                *(half8*)(yout + (long long)tq * C) = ov;
-            }
-        }
-    }
-}
-
 // Stride 1, a column of TH outputs per thread.  Consecutive threads own consecutive 16-byte chunks along an image
 // row (pixel-major, then channel group), so every load and store instruction of a wavefront covers one contiguous
 // kilobyte whatever the channel count; a thread fetches the left, centre and right vector of each of the TH + 2
-// input rows its column touches (the neighbours' copies of the same vectors hit in L1).  The strips of the kernels
+// input rows its column touches (the neighbours' copies of the same vectors hit in L1).  The strips of the kernel
 // above leave, with few channels, gaps of TW pixels between the lanes of one instruction.  Every output
 // accumulates its nine taps in the same order as there, so results are identical.
 template <int TH>
@@ -371,14 +285,10 @@ int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* 
     const long long total = (long long)N * P * ((Q + TW - 1) / TW) * (C / 8);
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffLL || (long long)N * P * ((Q + TW - 1) / TW) > 0xffffffffLL) { set_error("dwconv3x3: grid too large"); return -5; }
-    // two output rows per thread save a third of the loads, but halve the threads: only for grids that still fill the chip
-    const long long total2 = (long long)N * ((H + 1) / 2) * ((W + TW - 1) / TW) * (C / 8);
     constexpr int TH = 4;
     const long long total_cols = (long long)N * ((H + TH - 1) / TH) * W * (C / 8);
     if (stride == 1 && total_cols >= 16384 && (total_cols + 255) / 256 <= 0x7fffffffLL && (long long)N * ((H + TH - 1) / TH) * W <= 0xffffffffLL) {
         hipLaunchKernelGGL((dwconv3x3_s1_cols_kernel<TH>), dim3((unsigned)((total_cols + 255) / 256)), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, hp);
-    } else if (stride == 1 && H >= 2 && total2 >= 120000) {
-        hipLaunchKernelGGL((dwconv3x3_s1_2rows_kernel<TW>), dim3((unsigned)((total2 + 255) / 256)), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, hp);
     } else if (stride == 1)
         hipLaunchKernelGGL((dwconv3x3_kernel<1, TW>), dim3((unsigned)blocks), dim3(256), 0, stream, x, N, H, W, C, w_rsc, bias, act, y, P, Q, hp);
     else
