@@ -191,8 +191,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-by-batch", action="store_true")
     ap.add_argument("--no-gpu-state", action="store_true", help="skip the extra passes during which clocks are read (profiling runs count passes)")
-    ap.add_argument("--no-other-models", action="store_true", help="skip the VGG-19 and ViT-B/16 throughput lines")
-    ap.add_argument("--only-model", choices=("vgg19", "vit_b16"), default=None,
+    ap.add_argument("--no-other-models", action="store_true", help="skip the throughput lines of the other served models (VGG-19, ViT-B/16, MobileNetV2, encoder)")
+    ap.add_argument("--only-model", choices=("vgg19", "vit_b16", "mobilenet_v2", "encoder"), default=None,
                     help="time nothing but this model at batch 64 (for kernel profiles of the second workload set)")
     ap.add_argument("--colocation-seconds", type=float, default=5.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
@@ -254,7 +254,11 @@ def main() -> int:
     def other_model(arch, steps=20, warmup=5):
         omd, oblob = models_data(arch)
         om = ctx.load(oblob, max_batch=64, n_instances=1)
-        om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
+        if arch == synth.ARCH_ENCODER:
+            tokens, valid = synth.token_batch(omd, 64, 5)
+            om.copy_in(0, prio, tokens, valid)
+        else:
+            om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
         om.sync(0, prio)
         odt, odev = timed(om, 64, steps, warmup)
         macs = sum(l.macs_per_sample for l in om.layers())
@@ -264,7 +268,8 @@ def main() -> int:
         om.free()
         return res
 
-    others = {"vgg19": synth.ARCH_VGG19, "vit_b16": synth.ARCH_VIT}
+    # (for the encoder an "image" is a 128-token sequence with a seeded valid length)
+    others = {"vgg19": synth.ARCH_VGG19, "vit_b16": synth.ARCH_VIT, "mobilenet_v2": synth.ARCH_MOBILENETV2, "encoder": synth.ARCH_ENCODER}
     if args.only_model:
         # profiling aid: nothing but this model's steps is launched (no ResNet-50 step, no headline value)
         print(json.dumps({"only_model": args.only_model, "steps": K, "warmup": W, **other_model(others[args.only_model], K, W)}))
