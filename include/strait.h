@@ -133,6 +133,15 @@ strait_status strait_ctx_set_wave_priority(strait_ctx* ctx, int32_t enabled);
  * kernel-by-kernel path, bit for bit. */
 strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
 
+/* How inputs travel from the instance's pinned buffer to the device (Section 2 of the paper: inputs are
+ * "copied to the GPU's memory" before the kernels run; the first-in first-out link of Section 3.2).
+ * Inputs of at most max_bytes are read over the host link by a copy kernel on the copy stream; larger
+ * ones go by hipMemcpyAsync on the same stream.  Both sit between the same two events, so records and
+ * the link model see no difference.  Default 8 MiB (every serving-sized batch): under concurrent
+ * serving the asynchronous copy call of such sizes was measured to block its caller for milliseconds
+ * now and then, a kernel launch never.  0 = always hipMemcpyAsync. */
+strait_status strait_ctx_set_h2d_kernel_limit(strait_ctx* ctx, int64_t max_bytes);
+
 strait_status strait_model_load(strait_ctx* ctx, const strait_model_desc* desc, strait_model** out);
 strait_status strait_model_free(strait_model* m);       /* E_BUSY with batches in flight    */
 

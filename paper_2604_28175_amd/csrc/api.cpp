@@ -129,6 +129,13 @@ strait_status strait_ctx_set_graphs(strait_ctx* c, int32_t enabled) {
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_h2d_kernel_limit(strait_ctx* c, int64_t max_bytes) {
+    if (!c || max_bytes < 0) { set_error("ctx_set_h2d_kernel_limit: null context or negative size"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->h2d_kernel_limit = (size_t)max_bytes;
+    return STRAIT_OK;
+}
+
 static int hp_flag(const Context* c, int prio) { return prio == STRAIT_PRIO_HIGH && c->wave_priority; }
 
 // The kernel sequence of one batch on `s`: launched kernel by kernel, or, when the context asks for
@@ -312,9 +319,6 @@ static size_t compute_index(const Context* c, int prio, unsigned n) {
 
 // Stage the input in the instance's pinned buffer (no lock: this is the slow part and instances are
 // independent), then enqueue event / copy / event on copy stream `ci` as one uninterrupted group.
-// Largest input that is copied in by a kernel; above it the copy engines' bandwidth matters more than the rare stall.
-static constexpr size_t KERNEL_H2D_MAX_BYTES = 8u << 20;
-
 static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* host_in, const int32_t* valid_len, size_t ci) {
     Context* c = m->ctx;
     hipStream_t cs = c->copy[ci];
@@ -326,9 +330,11 @@ static int enqueue_h2d(strait_model* m, Instance& in, int batch, const void* hos
         pv = (int32_t*)((char*)in.pinned_in + off);
         for (int i = 0; i < batch; ++i) pv[i] = valid_len[i] < 0 ? 0 : (valid_len[i] > m->seq ? m->seq : valid_len[i]);
     }
+    size_t kernel_limit;
+    { std::lock_guard<std::mutex> ck(c->mu); kernel_limit = c->h2d_kernel_limit; }
     std::lock_guard<std::mutex> lk(c->copy_mu[ci]);
     HIP_TRY(hipEventRecord(in.ev_h2d0, cs));
-    if (inb <= KERNEL_H2D_MAX_BYTES && (inb & 3) == 0) {
+    if (inb <= kernel_limit && (inb & 3) == 0) {
         // inputs of serving-sized batches go in by a kernel that reads the pinned buffer over the host link: an
         // asynchronous copy call of this size now and then blocks its caller for milliseconds
         if (launch_copy_mapped(in.pinned_in_dev, in.dev_in, inb, 0, cs)) return STRAIT_E_HIP;

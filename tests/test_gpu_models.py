@@ -252,6 +252,25 @@ def test_small_batch_split_reduction_is_reproducible(ctx):
         m.free()
 
 
+def test_input_copy_by_kernel_and_by_copy_engine_give_the_same_result(ctx):
+    """Inputs up to a settable size go in by a copy kernel, larger ones by hipMemcpyAsync: same bytes on the device
+    either way, so outputs are identical bit for bit."""
+    md = synth.resnet50(4, hw=64)
+    m = ctx.load(synth.pack(md), max_batch=4, n_instances=1)
+    try:
+        x = synth.default_image_batch(md, 4, 3)
+        outs = []
+        for limit in (0, 8 << 20):
+            ctx.set_h2d_kernel_limit(limit)
+            out, rec = m.infer(x)
+            assert rec.h2d_ms > 0
+            outs.append(out)
+        assert np.array_equal(outs[0]["logits"], outs[1]["logits"]) and np.array_equal(outs[0]["top1"], outs[1]["top1"])
+    finally:
+        ctx.set_h2d_kernel_limit(8 << 20)
+        m.free()
+
+
 def test_submit_from_the_staging_buffer_makes_no_host_copy_and_gives_the_same_result(ctx):
     S = ctx.S
     md = synth.resnet50(4, hw=64)
