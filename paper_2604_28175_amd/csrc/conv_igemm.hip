@@ -657,17 +657,20 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(const ConvParams p) 
 // 3x3, stride 1, padding 1, from an input patch held in LDS.
 //
 // The kernel above fetches every input pixel nine times, once per filter tap; on the wide early layers that
-// traffic between L2 and LDS, not the MFMAs, sets the pace.  Here output pixels are numbered in the image with
-// its zero border, v = (n (H+2) + y) (W+2) + x, so that tap (r, s) of output v reads bordered input pixel
-// v + r (W+2) + s: one offset per tap for the whole tile.  A workgroup owns BM consecutive v (those with
-// y >= H or x >= W are computed and never stored) and BN output channels.  Per 32-channel slice of the input it
-// holds the BM + 2 (W+2) + 2 bordered pixels its taps touch (64 bytes each; border pixels arrive as zeros from
-// out-of-range transfers) and feeds all nine taps' MFMAs from them; only the weights, one 32-channel slice of
-// one tap at a time, stream through a three-stage ring.  The patch of the next slice arrives in a second buffer
-// during the first seven tap steps of the current one.  Per tap step every wave issues a fixed number of
-// transfers, so the in-order load counter tells when a given stage has landed.  LDS rows of 64 bytes are
-// swizzled as in the kernel above (16-byte chunk c of row i sits at c ^ ((i >> 2) & 3)), which keeps the
-// operand reads conflict free for any run of consecutive rows, i.e. for every tap offset.
+// traffic between L2 and LDS, not the MFMAs, sets the pace.  Here pixels are numbered in a bordered space: every
+// image row is preceded by one border slot and every image by one border row, v = (n (H+1) + y) (W+1) + x for
+// output (n, y, x), and the slot with number u holds input pixel (u's row - 1, u's column - 1) or, in the border,
+// zero.  A row's right border is the next row's left border and an image's bottom border row the next image's top
+// one, so one slot per row and one row per image suffice.  Tap (r, s) of output v then reads slot
+// v + r (W+1) + s: one offset per tap for the whole tile.  A workgroup owns BM consecutive v (the one in W+1 with
+// x = W and the one row in H+1 with y = H are computed and never stored) and BN output channels.  Per
+// 32-channel slice of the input it holds the BM + 2 (W+1) + 2 slots its taps touch (64 bytes each; border slots
+// arrive as zeros from out-of-range transfers) and feeds all nine taps' MFMAs from them; only the weights, one
+// 32-channel slice of one tap at a time, stream through a three-stage ring.  The patch of the next slice arrives
+// in a second buffer during the first seven tap steps of the current one.  Per tap step every wave issues a
+// fixed number of transfers, so the in-order load counter tells when a given stage has landed.  LDS rows of 64
+// bytes are swizzled as in the kernel above (16-byte chunk c of row i sits at c ^ ((i >> 2) & 3)), which keeps
+// the operand reads conflict free for any run of consecutive rows, i.e. for every tap offset.
 __device__ __forceinline__ void divmod_f(int v, int d, float rcp, int& q, int& r) {   // exact for 0 <= v < 2^24
     q = (int)((float)v * rcp);
     r = v - q * d;
@@ -718,10 +721,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
     const int tm = tile / tiles_n;
     const int m0 = tm * BM, n0 = (tile - tm * tiles_n) * BN;
 
-    // rows wider than 128 pixels are cut into strips, each numbered as an image of its own whose left and right
-    // "border" columns are the neighbouring strips' pixels (zeros only at the true edges)
-    const int SW = p.strip_w, NS = p.W / SW;
-    const int Wp = SW + 2, HpWp = (p.H + 2) * Wp, NI = (p.M / p.PQ) * NS;
+    // rows wider than 64 pixels are cut into strips, each numbered as an image of its own with a border slot on
+    // either side that holds the neighbouring strip's pixel (zero only at the true edges), so those are not shared
+    const int SW = p.strip_w, NS = __builtin_amdgcn_readfirstlane(p.W / SW);
+    const int Wp = SW + (NS == 1 ? 1 : 2), HpWp = (p.H + 1) * Wp, NI = (p.M / p.PQ) * NS;   // borders shared between neighbours
     const float rcp_w = 1.f / (float)Wp, rcp_i = 1.f / (float)HpWp, rcp_s = 1.f / (float)NS;
     const intx4 xrsrc = make_rsrc(p.x, (unsigned)(p.x_elems * 2));
     const intx4 wrsrc = make_rsrc(p.w, (unsigned)((long long)p.Cout * p.ldw * 2));
@@ -884,8 +887,8 @@ static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
     while (sw > 64 && sw % 2 == 0) sw /= 2;
     if (sw > 128) return -1;
     p.strip_w = sw;
-    const int wp = sw + 2;
-    const long long mv = (long long)(p.M / p.PQ) * (p.W / sw) * (p.H + 2) * wp;
+    const int wp = sw + (p.W == sw ? 1 : 2);
+    const long long mv = (long long)(p.M / p.PQ) * (p.W / sw) * (p.H + 1) * wp;
     if (mv >= (1LL << 24) - 4096) return -1;           // the kernel's index arithmetic is exact below 2^24
     auto per_wave = [&](int bm, int nw) { return ((bm + 2 * wp + 2 + 15) / 16 + nw - 1) / nw; };
     if (p.Cout % 128 == 0) {
@@ -1013,7 +1016,7 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
     }
     // wide 3x3 stride-1 layers: the patch kernel fetches each input pixel once per slice instead of once per tap
     if (staged && regular && small && mode == MODE_GATHER8 && p.R == 3 && p.S == 3 && p.stride_h == 1 && p.stride_w == 1 &&
-        p.pad_h == 1 && p.pad_w == 1 && !p.res && p.act != ACT_GELU && p.W >= 28 && p.Q == p.W && p.PQ == p.H * p.W && p.ldy % 8 == 0) {
+        p.pad_h == 1 && p.pad_w == 1 && !p.res && p.act != ACT_GELU && p.W >= 14 && p.Q == p.W && p.PQ == p.H * p.W && p.ldy % 8 == 0) {
         const int rc = launch_conv3x3_patch(p, stream);
         if (rc != -1) return rc;
     }
