@@ -88,7 +88,12 @@ def test_conv2d_integer_data_is_bit_exact(S):
 
 @pytest.mark.parametrize("N,H,W,C,K", [(4, 40, 60, 32, 64),      # 256-pixel tiles, one strip per row
                                        (2, 36, 128, 32, 128),    # rows cut into two strips of 64: the strips' side borders are real pixels
-                                       (1, 29, 224, 64, 64)])    # four strips of 56, two input slices
+                                       (1, 29, 224, 64, 64),     # four strips of 56, two input slices
+                                       (40, 15, 14, 32, 64),     # the narrowest rows served, odd height: shared borders everywhere
+                                       (30, 19, 17, 32, 128),    # odd width and height
+                                       (2, 70, 65, 32, 64),      # an odd width above 64 stays one strip
+                                       (2, 40, 130, 32, 64),     # two strips of odd width 65
+                                       (3, 21, 200, 32, 64)])    # four strips of 50
 def test_conv2d_wide_3x3_integer_data_is_bit_exact(S, N, H, W, C, K):
     """The wide 3x3 stride-1 layers run from an input patch in LDS, addressed through the bordered image: with
     integer data every border, strip seam and tile seam must come out exactly."""
