@@ -311,3 +311,103 @@ def test_vit_head_reads_the_class_token_after_the_final_norm():
     assert np.abs(full.logits - full.logits[0]).max() > 1e-6          # ... and not with the real blocks
     one = models.vit_forward(md.tensors, x[1:2], md.hyper)
     assert np.allclose(one.logits[0], full.logits[1], rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ wiring of whole blocks, with every branch live
+def _folded_unit(t, name, y, stride, pad):
+    """One convolution + folded BatchNorm from windows and one tensordot (not the oracle's loops)."""
+    w, b = ops.fold_bn(t[name + ".w"], t[name + ".gamma"], t[name + ".beta"], t[name + ".mean"], t[name + ".var"])
+    return conv_by_windows(y, w.astype(np.float64), b.astype(np.float64), stride, pad)
+
+
+def _depthwise_by_channels(t, name, y, stride):
+    """Depthwise 3x3 (pad 1) as one single-channel convolution per channel."""
+    w, b = ops.fold_bn(t[name + ".w"], t[name + ".gamma"], t[name + ".beta"], t[name + ".mean"], t[name + ".var"])
+    cols = [conv_by_windows(y[..., c:c + 1], w[c:c + 1].astype(np.float64), None, stride, 1) for c in range(y.shape[-1])]
+    return np.concatenate(cols, axis=-1) + b.astype(np.float64)
+
+
+def test_resnet50_bottleneck_wiring_identity_and_downsampling():
+    """A bottleneck with every convolution live: 1x1 -> ReLU -> 3x3 (carrying the stride) -> ReLU -> 1x1, plus the
+    block input (identity block) or its strided 1x1 projection (first block of a stage), then ReLU.  Recomposed from
+    the block's recorded input; a dropped ReLU, a dropped shortcut or a misplaced stride changes the result."""
+    md = synth.resnet50(9, hw=32)
+    t = md.tensors
+    x = synth.default_image_batch(md, 2, 3)
+    acts = models.resnet50_forward(t, x, keep=True).trace.acts
+    for p, src, stride, proj in (("s1b1", "s1b0.out", 1, False), ("s2b0", "s1b2.out", 2, True),
+                                 ("s1b0", "maxpool", 1, True), ("s4b2", "s4b1.out", 1, False)):
+        y = acts[src]
+        a = np.maximum(_folded_unit(t, p + ".c1", y, 1, 0), 0)
+        assert (a == 0).any() and (a > 0).any()                       # the clamp is exercised
+        a = np.maximum(_folded_unit(t, p + ".c2", a, stride, 1), 0)
+        a = _folded_unit(t, p + ".c3", a, 1, 0)
+        sc = _folded_unit(t, p + ".down", y, stride, 0) if proj else y
+        want = np.maximum(a + sc, 0)
+        got = acts[p + ".out"]
+        assert got.shape == want.shape and np.abs(a).max() > 1e-3     # the residual branch is not a zero
+        assert np.allclose(got, want, rtol=1e-10, atol=1e-10)
+        # ... and each of the mistakes named above would have been seen
+        assert not np.allclose(got, np.maximum(sc, 0), rtol=1e-6, atol=1e-6)
+        assert not np.allclose(got, np.maximum(a, 0), rtol=1e-6, atol=1e-6)
+
+
+def test_mobilenet_v2_inverted_residual_wiring():
+    """Inverted residual with every part live: 1x1 expansion -> ReLU6 -> depthwise 3x3 (stride) -> ReLU6 -> linear 1x1
+    projection, plus the block input when the stride is 1 and the widths agree.  One stride-1 block with a residual
+    connection, one stride-2 block, and the first block (no expansion)."""
+    md = synth.mobilenet_v2(4, hw=64)
+    t = md.tensors
+    x = synth.default_image_batch(md, 2, 3)
+    acts = models.mobilenet_v2_forward(t, x, keep=True).trace.acts
+    hit0 = hit6 = False
+    for p, src, stride, expand, residual in (("b2", "b1.project", 1, True, True), ("b3", "b2.out", 2, True, False),
+                                             ("b0", "stem", 1, False, False), ("b5", "b4.out", 1, True, True)):
+        y = acts[src]
+        a = y
+        if expand:
+            a = np.clip(_folded_unit(t, p + ".expand", a, 1, 0), 0, 6)
+            hit0 |= bool((a == 0).any()); hit6 |= bool((a == 6).any())
+        a = np.clip(_depthwise_by_channels(t, p + ".dw", a, stride), 0, 6)
+        hit0 |= bool((a == 0).any()); hit6 |= bool((a == 6).any())
+        a = _folded_unit(t, p + ".project", a, 1, 0)                  # linear bottleneck: no clamp here
+        assert (a < 0).any()
+        want = a + y if residual else a
+        got = acts[p + ".out"] if residual else acts[p + ".project"]
+        assert got.shape == want.shape
+        assert np.allclose(got, want, rtol=1e-10, atol=1e-10)
+        if residual:
+            assert not np.allclose(got, a, rtol=1e-6, atol=1e-6)
+    assert hit0 and hit6                                              # both clamps of ReLU6 were exercised
+
+
+def test_encoder_layer_matches_the_library_post_norm_layer():
+    """torch.nn.TransformerEncoderLayer(norm_first=False, activation='gelu') with a key-padding mask is the same
+    layer: x -> LN(x + Attn(x)) -> LN(h + FFN(h)).  Rows at valid positions are compared, layer by layer."""
+    import torch
+    md = synth.encoder(6, layers=2, hidden=32, heads=2, ffn=64, seq=12)
+    x, vl = synth.token_batch(md, 3, 8, min_len=4)
+    assert vl.min() < 12                                              # some keys are masked
+    t = md.tensors
+    r = models.encoder_forward(t, x, vl, md.hyper, keep=True)
+    layer = torch.nn.TransformerEncoderLayer(32, 2, 64, dropout=0.0, activation="gelu", layer_norm_eps=1e-12,
+                                             batch_first=True, norm_first=False).double().train()
+    pad = torch.from_numpy(np.arange(12)[None, :] >= vl[:, None])
+    z = torch.from_numpy(np.asarray(x, np.float64))
+    f64 = lambda k: torch.from_numpy(t[k].astype(np.float64))
+    for i in range(2):
+        p = f"l{i}"
+        layer.load_state_dict({
+            "self_attn.in_proj_weight": torch.cat([f64(p + ".q.w"), f64(p + ".k.w"), f64(p + ".v.w")]),
+            "self_attn.in_proj_bias": torch.cat([f64(p + ".q.b"), f64(p + ".k.b"), f64(p + ".v.b")]),
+            "self_attn.out_proj.weight": f64(p + ".o.w"), "self_attn.out_proj.bias": f64(p + ".o.b"),
+            "linear1.weight": f64(p + ".ffn1.w"), "linear1.bias": f64(p + ".ffn1.b"),
+            "linear2.weight": f64(p + ".ffn2.w"), "linear2.bias": f64(p + ".ffn2.b"),
+            "norm1.weight": f64(p + ".ln1.g"), "norm1.bias": f64(p + ".ln1.b"),
+            "norm2.weight": f64(p + ".ln2.g"), "norm2.bias": f64(p + ".ln2.b")})
+        with torch.no_grad():
+            z = layer(z, src_key_padding_mask=pad)
+        got = r.trace.acts[p + ".ln2"]
+        for b in range(3):
+            assert np.allclose(z.numpy()[b, :vl[b]], got[b, :vl[b]], rtol=1e-9, atol=1e-10)
+    assert np.array_equal(r.logits, r.trace.acts["l1.ln2"])
