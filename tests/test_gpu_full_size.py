@@ -82,9 +82,9 @@ def test_encoder_all_batches(ctx):
 
 
 def test_vgg19_full_size(ctx):
-    cnn_case(ctx, synth.ARCH_VGG19, omodels.vgg19_forward, (1, 6))
+    cnn_case(ctx, synth.ARCH_VGG19, omodels.vgg19_forward, (1, 6, 64))      # 64: the batch the benchmark times
 
 
 def test_vit_b16_full_size(ctx):
     md_hyper = (224, 224, 3, 1000, 12, 768, 12, 3072)                 # what synth.vit() draws by default
-    cnn_case(ctx, synth.ARCH_VIT, lambda t, x: omodels.vit_forward(t, x, md_hyper), (1, 8, 19))
+    cnn_case(ctx, synth.ARCH_VIT, lambda t, x: omodels.vit_forward(t, x, md_hyper), (1, 8, 19, 64))

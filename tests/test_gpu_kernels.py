@@ -54,6 +54,11 @@ CONV_CASES = [
     (1, 37, 112, 64, 128, 3, 1, 1, 0, False, False),    # wider rows (larger patch), ragged height, no activation
     (2, 24, 224, 32, 64, 3, 1, 1, 1, False, False),     # widest rows served: the largest patch
     (2, 40, 100, 96, 192, 3, 1, 1, 2, False, False),    # three channel tiles, three input slices, ReLU6
+    # enough 256 x 128 tiles (768 or more) for the eight-wave form of that kernel, in both of its patch sizes
+    (64, 56, 56, 32, 256, 3, 1, 1, 1, False, False),    # 1626 tiles, three patch transfers per wave, two channel tiles
+    (16, 112, 112, 64, 128, 3, 1, 1, 1, False, False),  # rows cut into two strips of 56; two input slices
+    (48, 64, 64, 32, 128, 3, 1, 1, 0, False, False),    # 64-pixel rows: four patch transfers per wave
+    (12, 128, 128, 32, 128, 3, 1, 1, 2, False, False),  # two strips of 64: four transfers per wave with real pixels on the strips' sides
 ]
 
 
@@ -93,7 +98,9 @@ def test_conv2d_integer_data_is_bit_exact(S):
                                        (30, 19, 17, 32, 128),    # odd width and height
                                        (2, 70, 65, 32, 64),      # an odd width above 64 stays one strip
                                        (2, 40, 130, 32, 64),     # two strips of odd width 65
-                                       (3, 21, 200, 32, 64)])    # four strips of 50
+                                       (3, 21, 200, 32, 64),     # four strips of 50
+                                       # the eight-wave 256 x 128 tile (768 tiles or more): three and four patch transfers per wave
+                                       (64, 56, 56, 32, 256), (16, 112, 112, 32, 128), (48, 64, 64, 32, 128), (12, 128, 128, 64, 128)])
 def test_conv2d_wide_3x3_integer_data_is_bit_exact(S, N, H, W, C, K):
     """The wide 3x3 stride-1 layers run from an input patch in LDS, addressed through the bordered image: with
     integer data every border, strip seam and tile seam must come out exactly."""
