@@ -210,6 +210,16 @@ strait_status strait_k_conv2d(void* stream, const void* x, int32_t N, int32_t H,
 strait_status strait_k_gemm(void* stream, const void* x, const void* w, const float* bias, int32_t M,
                             int32_t N, int32_t K, int32_t act, const void* res, void* y, int32_t out_f32,
                             int32_t hp);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): strait_k_gemm for products of at most 128 * 4096 outputs (M * N; E_SHAPE beyond -- larger products
+ * use no workspace and strait_k_gemm allocates nothing for them), with the split-K workspace of 16 MiB taken from a
+ * static device array instead of hipMalloc.  Same kernels, same results bit for bit.  Calls no allocating routine and
+ * does not synchronise; the launch is asynchronous on `stream`, whose device must be the current one.  Every call on
+ * a GPU shares that GPU's array (held until the process ends), so calls that overlap on one GPU race; calls ordered
+ * by a stream or an event do not. */
+strait_status strait_k_gemm_noalloc(void* stream, const void* x, const void* w, const float* bias, int32_t M,
+                                    int32_t N, int32_t K, int32_t act, const void* res, void* y, int32_t out_f32,
+                                    int32_t hp);
 /* Depthwise 3x3: y[n,p,q,c] = act(bias[c] + sum_{r,s} x[..,c] * w[r][s][c]); w fp16 [3][3][C]; C % 8 == 0. */
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,

@@ -86,6 +86,7 @@ _SIGS = {
     "strait_read_activation": (_i32, [_vp, _i32, _i32, _i32, _vp, _sz, C.POINTER(_sz)]),
     "strait_k_conv2d": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
+    "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_stem_pool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _i32]),
@@ -348,6 +349,15 @@ def k_gemm(x, w, bias, act=ACT_NONE, res=None, out_f32=False, hp=0, stream=None)
     n = w.shape[0]
     y = torch.empty((m, n), dtype=torch.float32 if out_f32 else torch.float16, device=x.device)
     _check(lib.strait_k_gemm(_stream(stream), _dev(x), _dev(w), _dev(bias), m, n, k, act, _dev(res), _dev(y), int(out_f32), hp))
+    return y
+
+
+def k_gemm_noalloc(x, w, bias, y, act=ACT_NONE, res=None, out_f32=False, hp=0, stream=None):
+    """strait_k_gemm_noalloc into the caller's output tensor `y` (nothing is allocated on the way)."""
+    m, k = x.shape
+    n = w.shape[0]
+    assert tuple(y.shape) == (m, n)
+    _check(lib.strait_k_gemm_noalloc(_stream(stream), _dev(x), _dev(w), _dev(bias), m, n, k, act, _dev(res), _dev(y), int(out_f32), hp))
     return y
 
 
