@@ -152,10 +152,7 @@ class SchedulerOracle:
         r = self.running[gpu].pop(rid)
         m_avg = self.track[gpu].depart(rid, now)
         if h2d_end_ns is not None:
-            try:
-                self.links[gpu].complete(r["link_id"], h2d_end_ns)
-            except Exception:
-                pass
+            self.links[gpu].complete(r["link_id"], h2d_end_ns)       # an unknown transfer id is an error and surfaces
         actual = kernel_ns / r["prof"].t_kernel_isol
         loss = self.pred.update(m_avg, r["prof"].self_cmp, r["prof"].self_mem, r["prio"], actual)
         violated = now > r["deadline"]

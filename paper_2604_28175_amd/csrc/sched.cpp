@@ -68,6 +68,10 @@ struct Sched {
         }
         return false;
     }
+    // Eq. 1 for a candidate batch.  Its co-located pressure over its coming life is unknown at scheduling time; the
+    // paper's meet() (Section 3.3) settles it by judging the batch "under half of that GPU's runtime throughput", so
+    // Eq. 4 is fed half of the summed demand of the batches running on the GPU now.  (violate() is different on
+    // purpose: for batches already running it uses the full pressure with the candidate added.)
     double t_inf(int g, int prio, const Profile& np, int64_t now, int64_t t_queue) const {
         const int64_t t_data = links[g].predict(now);
         double half[NM];
