@@ -133,6 +133,11 @@ strait_status strait_ctx_set_wave_priority(strait_ctx* ctx, int32_t enabled);
  * kernel-by-kernel path, bit for bit. */
 strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
 
+/* Whether a plan's independent branches (the projection shortcut of a residual stage's first block) run on the
+ * instance's side stream beside the main sequence (default on).  Off keeps every launch on the one compute stream, in
+ * plan order: kernel traces of such a run add up to the step time. */
+strait_status strait_ctx_set_branch_streams(strait_ctx* ctx, int32_t enabled);
+
 /* How inputs travel from the instance's pinned buffer to the device (Section 2 of the paper: inputs are
  * "copied to the GPU's memory" before the kernels run; the first-in first-out link of Section 3.2).
  * Inputs of at most max_bytes are read over the host link by a copy kernel on the copy stream; larger

@@ -69,6 +69,7 @@ _SIGS = {
     "strait_ctx_set_wave_priority": (_i32, [_vp, _i32]),
     "strait_ctx_set_graphs": (_i32, [_vp, _i32]),
     "strait_ctx_set_h2d_kernel_limit": (_i32, [_vp, C.c_int64]),
+    "strait_ctx_set_branch_streams": (_i32, [_vp, _i32]),
     "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
     "strait_model_free": (_i32, [_vp]),
     "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
@@ -181,6 +182,9 @@ class Context:
 
     def set_graphs(self, enabled: bool):
         _check(lib.strait_ctx_set_graphs(self.handle, 1 if enabled else 0))
+
+    def set_branch_streams(self, enabled: bool):
+        _check(lib.strait_ctx_set_branch_streams(self.handle, 1 if enabled else 0))
 
     def set_h2d_kernel_limit(self, max_bytes: int):
         _check(lib.strait_ctx_set_h2d_kernel_limit(self.handle, int(max_bytes)))

@@ -136,6 +136,13 @@ strait_status strait_ctx_set_h2d_kernel_limit(strait_ctx* c, int64_t max_bytes) 
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_branch_streams(strait_ctx* c, int32_t enabled) {
+    if (!c) { set_error("ctx_set_branch_streams: null"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->branch_streams = enabled != 0;
+    return STRAIT_OK;
+}
+
 static int hp_flag(const Context* c, int prio) { return prio == STRAIT_PRIO_HIGH && c->wave_priority; }
 
 // The kernel sequence of one batch on `s`: launched kernel by kernel, or, when the context asks for

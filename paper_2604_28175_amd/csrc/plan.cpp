@@ -850,7 +850,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     const int n = (int)m.ops.size();
     if (last_layer < 0 || last_layer >= n) last_layer = n - 1;
     // Per-layer timing and prefix runs keep everything on the one stream (their events bracket single launches).
-    const bool branches = !timed && last_layer == n - 1 && in.side != nullptr;
+    const bool branches = !timed && last_layer == n - 1 && in.side != nullptr && m.ctx->branch_streams;
     bool forked = false;
     hipStream_t main_stream = stream;
     for (int i = 0; i <= last_layer; ++i) {

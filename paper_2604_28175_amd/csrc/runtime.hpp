@@ -131,6 +131,7 @@ struct Context {
     bool stop = false;
     bool wave_priority = true;
     bool use_graphs = false;
+    bool branch_streams = true;             // independent branches of a plan go to the instance's side stream
     size_t h2d_kernel_limit = 8u << 20;   // inputs up to this size go in by a copy kernel, larger ones by hipMemcpyAsync
     unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;
     int n_models = 0, next_model_id = 0;
