@@ -133,6 +133,12 @@ strait_status strait_ctx_set_wave_priority(strait_ctx* ctx, int32_t enabled);
  * kernel-by-kernel path, bit for bit. */
 strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
 
+/* From how many output pixels (batch x height x width) on a residual block's closing 1x1 convolution and the next
+ * block's opening 1x1 convolution, which reads nothing but the first one's output, run as one launch
+ * (strait_k_pointwise_pair).  Default 200000 (ResNet-50 at batch 64 and above: each wavefront then walks over several
+ * tiles, which pays for loading the weights into LDS once per workgroup); 0 = always two launches.  Results are the
+ * same bit for bit. */
+strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
 /* Whether a plan's independent branches (the projection shortcut of a residual stage's first block) run on the
  * instance's side stream beside the main sequence (default on).  Off keeps every launch on the one compute stream, in
  * plan order: kernel traces of such a run add up to the step time. */
@@ -225,6 +231,16 @@ strait_status strait_k_gemm(void* stream, const void* x, const void* w, const fl
 strait_status strait_k_gemm_noalloc(void* stream, const void* x, const void* w, const float* bias, int32_t M,
                                     int32_t N, int32_t K, int32_t act, const void* res, void* y, int32_t out_f32,
                                     int32_t hp);
+/* Two chained pointwise convolutions in one launch (Section 3.2 step (2): consecutive kernels of a batch's sequence):
+ *     y[m, 0:N1] = act1(x[m, 0:K1] w3^T + b3 (+ res[m, 0:N1]));     z[m, 0:N2] = act2(y[m, 0:N1] w1^T + b1)
+ * x [M][K1], w3 [N1][K1], res (or NULL) and y [M][N1], w1 [N2][N1], z [M][N2], dense fp16; b3 [N1], b1 [N2] fp32 or NULL;
+ * act1/act2 NONE, RELU or RELU6.  res is required.  K1 = 64, N1 = 256, N2 in {64, 128}: the shapes whose two weight
+ * matrices fit in a compute unit's LDS together (E_SHAPE otherwise).  y is
+ * rounded to fp16 before it enters the second product, as if the two layers had run one after the other.  z must not
+ * overlap x or res. */
+strait_status strait_k_pointwise_pair(void* stream, const void* x, const void* w3, const float* b3, const void* res, void* y,
+                                      const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t N1, int32_t N2,
+                                      int32_t act1, int32_t act2, int32_t hp);
 /* Depthwise 3x3: y[n,p,q,c] = act(bias[c] + sum_{r,s} x[..,c] * w[r][s][c]); w fp16 [3][3][C]; C % 8 == 0. */
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,

@@ -70,6 +70,7 @@ _SIGS = {
     "strait_ctx_set_graphs": (_i32, [_vp, _i32]),
     "strait_ctx_set_h2d_kernel_limit": (_i32, [_vp, C.c_int64]),
     "strait_ctx_set_branch_streams": (_i32, [_vp, _i32]),
+    "strait_ctx_set_pair_fusion": (_i32, [_vp, _i64]),
     "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
     "strait_model_free": (_i32, [_vp]),
     "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
@@ -88,6 +89,7 @@ _SIGS = {
     "strait_k_conv2d": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
+    "strait_k_pointwise_pair": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_stem_pool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _i32]),
@@ -182,6 +184,9 @@ class Context:
 
     def set_graphs(self, enabled: bool):
         _check(lib.strait_ctx_set_graphs(self.handle, 1 if enabled else 0))
+
+    def set_pair_fusion(self, min_pixels: int):
+        _check(lib.strait_ctx_set_pair_fusion(self.handle, int(min_pixels)))
 
     def set_branch_streams(self, enabled: bool):
         _check(lib.strait_ctx_set_branch_streams(self.handle, 1 if enabled else 0))
@@ -363,6 +368,17 @@ def k_gemm_noalloc(x, w, bias, y, act=ACT_NONE, res=None, out_f32=False, hp=0, s
     assert tuple(y.shape) == (m, n)
     _check(lib.strait_k_gemm_noalloc(_stream(stream), _dev(x), _dev(w), _dev(bias), m, n, k, act, _dev(res), _dev(y), int(out_f32), hp))
     return y
+
+
+def k_pointwise_pair(x, w3, b3, res, w1, b1, act1=ACT_RELU, act2=ACT_RELU, hp=0, stream=None):
+    import torch
+    m, k1 = x.shape
+    n1, n2 = w3.shape[0], w1.shape[0]
+    y = torch.empty((m, n1), dtype=torch.float16, device=x.device)
+    z = torch.empty((m, n2), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_pointwise_pair(_stream(stream), _dev(x), _dev(w3), _dev(b3), _dev(res), _dev(y), _dev(w1), _dev(b1),
+                                       _dev(z), m, k1, n1, n2, act1, act2, hp))
+    return y, z
 
 
 def k_dwconv3x3(x, w_rsc, bias, stride, act=ACT_NONE, hp=0, stream=None):

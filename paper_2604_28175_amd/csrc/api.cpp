@@ -136,6 +136,13 @@ strait_status strait_ctx_set_h2d_kernel_limit(strait_ctx* c, int64_t max_bytes) 
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_pair_fusion(strait_ctx* c, int64_t min_pixels) {
+    if (!c || min_pixels < 0) { set_error("ctx_set_pair_fusion: null context or negative size"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->pair_min_pixels = min_pixels;
+    return STRAIT_OK;
+}
+
 strait_status strait_ctx_set_branch_streams(strait_ctx* c, int32_t enabled) {
     if (!c) { set_error("ctx_set_branch_streams: null"); return STRAIT_E_INVALID; }
     std::lock_guard<std::mutex> lk(c->mu);
@@ -584,6 +591,16 @@ strait_status strait_k_gemm(void* stream, const void* x, const void* w, const fl
     int rc = launch_conv(p, (hipStream_t)stream);
     if (ws) { (void)hipStreamSynchronize((hipStream_t)stream); (void)hipFree(ws); }
     return rc;
+}
+
+strait_status strait_k_pointwise_pair(void* stream, const void* x, const void* w3, const float* b3, const void* res, void* y,
+                                      const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t N1, int32_t N2,
+                                      int32_t act1, int32_t act2, int32_t hp) {
+    PairParams p{};
+    p.x = (const half_t*)x; p.w3 = (const half_t*)w3; p.b3 = b3; p.res = (const half_t*)res; p.y = (half_t*)y;
+    p.w1 = (const half_t*)w1; p.b1 = b1; p.z = (half_t*)z;
+    p.M = M; p.K1 = K1; p.N1 = N1; p.N2 = N2; p.act1 = act1; p.act2 = act2; p.hp = hp;
+    return launch_pointwise_pair(p, (hipStream_t)stream);
 }
 
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,

@@ -46,6 +46,18 @@ struct ConvParams {
 
 int launch_conv(const ConvParams& p, hipStream_t stream);
 
+// Two chained pointwise convolutions in one launch (pointwise_pair.hip):
+//   y[m, 0:N1] = act1(x[m, 0:K1] w3^T + b3 (+ res[m, 0:N1]));   z[m, 0:N2] = act2(y[m, 0:N1] w1^T + b1)
+// x [M][K1], w3 [N1][K1], res and y [M][N1], w1 [N2][N1], z [M][N2], all dense fp16; biases fp32 or nullptr.
+// z must not share memory with x or res (other workgroups may still be reading them).
+struct PairParams {
+    const half_t* x; const half_t* w3; const float* b3; const half_t* res; half_t* y;
+    const half_t* w1; const float* b1; half_t* z;
+    int M, K1, N1, N2, act1, act2, hp;
+};
+bool pointwise_pair_supported(int K1, int N1, int N2);
+int launch_pointwise_pair(const PairParams& p, hipStream_t stream);
+
 int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, int Hp, int Wp, int Cpad,
                       int pad_top, int pad_left, int hp, hipStream_t stream);
 // 7x7 stride-2 pad-3 convolution of a 3-channel image to 64 channels + bias + ReLU + 3x3 stride-2 pad-1 max pooling.

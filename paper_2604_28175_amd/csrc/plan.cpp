@@ -533,6 +533,7 @@ static int plan_resnet50(Model& m, Builder& b) {
     }
     int cin = 64;
     const int nblocks[4] = {3, 4, 6, 3}, planes[4] = {64, 128, 256, 512};
+    int carry_t1 = -1;                                  // output buffer of the next block's c1 when it may be fused with this block's c3
     for (int si = 0; si < 4; ++si)
         for (int bi = 0; bi < nblocks[si]; ++bi) {
             char pre[16];
@@ -548,7 +549,8 @@ static int plan_resnet50(Model& m, Builder& b) {
                 if ((rc = b.conv(p + ".down", true, cur, P, Q, cin, pln * 4, 1, stride, 0, ACT_NONE, SLOT_NONE, sc, nullptr, nullptr))) return rc;
                 m.ops.back().side = 1;
             }
-            const int t1 = b.pl.get((size_t)P * Q * pln);
+            const int t1 = carry_t1 >= 0 ? carry_t1 : b.pl.get((size_t)P * Q * pln);
+            carry_t1 = -1;
             if ((rc = b.conv(p + ".c1", true, cur, P, Q, cin, pln, 1, 1, 0, ACT_RELU, SLOT_NONE, t1, nullptr, nullptr))) return rc;
             const int t2 = b.pl.get((size_t)P2 * Q2 * pln);
             if ((rc = b.conv(p + ".c2", true, t1, P, Q, pln, pln, 3, stride, 1, ACT_RELU, SLOT_NONE, t2, nullptr, nullptr))) return rc;
@@ -557,6 +559,15 @@ static int plan_resnet50(Model& m, Builder& b) {
             const int o = b.pl.get((size_t)P2 * Q2 * pln * 4);
             if ((rc = b.conv(p + ".c3", true, t2, P2, Q2, pln, pln * 4, 1, 1, 0, ACT_RELU, sc, o, nullptr, nullptr))) return rc;
             if (bi == 0) m.ops.back().join = 1;
+            // This c3 and the next block's c1 can run as one launch.  That launch writes the c1 output while other
+            // workgroups still read this block's c2 output and shortcut, so its buffer is taken before those two are
+            // released (it must not reuse them).  The next block's projection shortcut, if any, sits between the two ops.
+            const bool last = si == 3 && bi == nblocks[si] - 1;
+            const int next_pln = bi == nblocks[si] - 1 ? (si < 3 ? planes[si + 1] : 0) : pln;
+            if (!last && pointwise_pair_supported(pln, pln * 4, next_pln) && m.ops.back().ldw == pln) {
+                carry_t1 = b.pl.get((size_t)P2 * Q2 * next_pln);
+                m.ops.back().pair = bi == nblocks[si] - 1 ? 2 : 1;
+            }
             b.pl.put(t2);
             b.pl.put(sc);
             cur = o; cin = pln * 4; P = P2; Q = Q2;
@@ -853,9 +864,14 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     const bool branches = !timed && last_layer == n - 1 && in.side != nullptr && m.ctx->branch_streams;
     bool forked = false;
     hipStream_t main_stream = stream;
+    int fused_away = -1;                                // op already computed by the pair launch of an earlier op
     for (int i = 0; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
         stream = main_stream;
+        if (i == fused_away) {
+            if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
+            continue;
+        }
         // a branch pays a fork and a join (two event hand-overs between streams): only worth it for a launch
         // of some size; smaller ones stay in line, where they may also split their reduction
         if (branches && op.side && (long long)batch * op.P * op.Q * op.K >= 8000000LL) {
@@ -875,6 +891,18 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
         int rc = 0;
         switch (op.kind) {
             case OP_CONV: {
+                if (op.pair && i + op.pair <= last_layer && m.ctx->pair_min_pixels > 0 && (long long)batch * op.P * op.Q >= m.ctx->pair_min_pixels) {
+                    const Op& nx = m.ops[i + op.pair];
+                    PairParams q{};
+                    q.x = (const half_t*)src; q.w3 = op.w; q.b3 = op.bias;
+                    q.res = (const half_t*)slot_ptr(m, in, op.res, 0, batch);
+                    q.y = (half_t*)dst;
+                    q.w1 = nx.w; q.b1 = nx.bias; q.z = (half_t*)slot_ptr(m, in, nx.out, nx.out_ref, batch);
+                    q.M = batch * op.P * op.Q; q.K1 = op.vC; q.N1 = op.K; q.N2 = nx.K; q.act1 = op.act; q.act2 = nx.act; q.hp = hp;
+                    rc = launch_pointwise_pair(q, stream);
+                    fused_away = i + op.pair;
+                    break;
+                }
                 ConvParams p{};
                 p.x = (const half_t*)src; p.w = op.w; p.bias = op.bias;
                 p.res = (const half_t*)slot_ptr(m, in, op.res, 0, batch);

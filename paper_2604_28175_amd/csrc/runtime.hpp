@@ -42,6 +42,9 @@ struct Op {
     // Independent branch: `side` ops run on the instance's side stream, forked off the main stream right
     // before them; the first later op with `join` set waits for the side stream before it is launched.
     int side = 0, join = 0;
+    // A block-closing pointwise convolution whose output feeds the pointwise convolution `pair` ops further on (0 = none):
+    // at large batches the two run as one launch (pointwise_pair.hip) and the second op is skipped.
+    int pair = 0;
     // implicit-GEMM addressing (elements), see ConvParams
     long long sN = 0; int sH = 0, sW = 0, stride_w = 1, pad_h = 0, pad_w = 0, vC = 0, vR = 0, vS = 0, vH = 0, vW = 0;
     int ldw = 0;
@@ -131,6 +134,7 @@ struct Context {
     bool stop = false;
     bool wave_priority = true;
     bool use_graphs = false;
+    long long pair_min_pixels = 200000;     // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
     bool branch_streams = true;             // independent branches of a plan go to the instance's side stream
     size_t h2d_kernel_limit = 8u << 20;   // inputs up to this size go in by a copy kernel, larger ones by hipMemcpyAsync
     unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;

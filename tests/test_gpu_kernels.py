@@ -136,6 +136,72 @@ def test_gemm(S, M, N, K, act, use_res, out_f32):
     check_kernel(y.float().cpu().numpy(), ref, f"gemm {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,K1,N1,N2,use_res", [(9001, 64, 256, 64, True),       # many 32-pixel tiles and a ragged tail
+                                                 (5000, 64, 256, 128, True),      # the seam into the next stage: twice as wide
+                                                 (70, 64, 256, 64, True),         # fewer tiles than one workgroup has wavefronts
+                                                 (97001, 64, 256, 64, True),      # every wavefront of the full grid walks over several tiles
+                                                 (70003, 64, 256, 128, True)])
+def test_pointwise_pair(S, M, K1, N1, N2, use_res):
+    """y = relu(x W3^T + b3 + res), z = relu(fp16(y) W1^T + b1) in one launch: against the oracle's operators, and bit
+    for bit against the same two layers as two launches."""
+    x = f16(R.standard_normal((M, K1)))
+    w3 = f16(R.standard_normal((N1, K1)) * (0.5 / K1) ** 0.5)
+    b3 = (R.standard_normal(N1) * 0.1).astype(np.float32)
+    res = f16(R.standard_normal((M, N1))) if use_res else None
+    w1 = f16(R.standard_normal((N2, N1)) * (2.0 / N1) ** 0.5)
+    b1 = (R.standard_normal(N2) * 0.1).astype(np.float32)
+    y_ref = ops.linear(x, w3, b3)
+    if use_res:
+        y_ref = y_ref + res.astype(np.float64)
+    y_ref = ops.relu(y_ref)
+    z_ref = ops.relu(ops.linear(y_ref.astype(np.float16), w1, b1))      # the second layer reads the fp16 tensor
+    dx, dw3, db3, dw1, db1 = dev(S, x), dev(S, w3), dev(S, b3), dev(S, w1), dev(S, b1)
+    dres = None if res is None else dev(S, res)
+    y, z = S.k_pointwise_pair(dx, dw3, db3, dres, dw1, db1)
+    S.torch.cuda.synchronize()
+    check_kernel(y.float().cpu().numpy(), y_ref, f"pair y {M}x{K1}x{N1}")
+    check_kernel(z.float().cpu().numpy(), z_ref, f"pair z {M}x{N1}x{N2}", rel=2.0 ** -9)
+    y2 = S.k_gemm(dx, dw3, db3, S.ACT_RELU, dres)
+    assert S.torch.equal(y, y2)
+    if M * N2 > 128 * 4096:           # (below that the stand-alone kernel splits its reduction and adds in another order)
+        assert S.torch.equal(z, S.k_gemm(y2, dw1, db1, S.ACT_RELU))
+
+
+def test_pointwise_pair_integer_data_is_bit_exact(S):
+    M, K1, N1, N2 = 777, 64, 256, 64
+    x = R.integers(-2, 3, (M, K1)).astype(np.float16)
+    w3 = R.integers(-1, 2, (N1, K1)).astype(np.float16)
+    b3 = R.integers(-3, 4, N1).astype(np.float32)
+    res = R.integers(-4, 5, (M, N1)).astype(np.float16)
+    w1 = (R.integers(-1, 2, (N2, N1)) * (R.random((N2, N1)) < 0.1)).astype(np.float16)     # sparse: sums stay exact in fp16
+    b1 = R.integers(-3, 4, N2).astype(np.float32)
+    y_ref = ops.relu(ops.linear(x, w3, b3) + res.astype(np.float64))
+    z_ref = ops.relu(ops.linear(y_ref, w1, b1))
+    assert np.abs(y_ref).max() < 2048 and np.abs(z_ref).max() < 2048
+    y, z = S.k_pointwise_pair(dev(S, x), dev(S, w3), dev(S, b3), dev(S, res), dev(S, w1), dev(S, b1))
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), y_ref)
+    assert np.array_equal(z.float().cpu().numpy().astype(np.float64), z_ref)
+
+
+def test_pointwise_pair_rejects_other_shapes(S):
+    t = S.torch.zeros((256, 96), dtype=S.torch.float16, device="cuda")
+    w3 = S.torch.zeros((256, 96), dtype=S.torch.float16, device="cuda")
+    w1 = S.torch.zeros((64, 256), dtype=S.torch.float16, device="cuda")
+    res = S.torch.zeros((256, 256), dtype=S.torch.float16, device="cuda")
+    with pytest.raises(S.StraitError) as e:
+        S.k_pointwise_pair(t, w3, None, res, w1, None)             # 96 input channels
+    assert e.value.status == S.E_SHAPE
+    with pytest.raises(S.StraitError) as e:
+        S.k_pointwise_pair(S.torch.zeros((256, 128), dtype=S.torch.float16, device="cuda"),
+                           S.torch.zeros((512, 128), dtype=S.torch.float16, device="cuda"), None,
+                           S.torch.zeros((256, 512), dtype=S.torch.float16, device="cuda"),
+                           S.torch.zeros((128, 512), dtype=S.torch.float16, device="cuda"), None)   # weights that do not fit in LDS
+    assert e.value.status == S.E_SHAPE
+    with pytest.raises(S.StraitError) as e:
+        S.k_pointwise_pair(t[:, :64].contiguous(), w3[:, :64].contiguous(), None, None, w1, None)   # no residual tensor
+    assert e.value.status == S.E_INVALID
+
+
 @pytest.mark.parametrize("N,H,W,C,stride", [(2, 14, 14, 96, 1), (2, 15, 13, 144, 2), (1, 7, 7, 960, 1), (3, 28, 28, 32, 2), (1, 9, 10, 8, 1),
                                             # stride 1 with enough work for the column kernel: few channels, ragged height, many channels
                                             (6, 56, 56, 32, 1), (5, 30, 27, 144, 1), (16, 7, 7, 960, 1)])

@@ -84,6 +84,31 @@ def test_resnet50_layers_and_batch_independence(ctx):
     m.free()
 
 
+def test_resnet50_fused_block_seams_equal_separate_launches(ctx):
+    """The closing 1x1 of a bottleneck and the opening 1x1 of the next one as one launch (forced at every size here,
+    ragged tiles included) give the logits of the layer-by-layer plan bit for bit, and the oracle's within tolerance."""
+    md = synth.resnet50(5)            # full size, six images: no layer of a fused pair is small enough to split its reduction
+    x = synth.default_image_batch(md, 6, 9)
+    m = ctx.load(synth.pack(md), max_batch=6, n_instances=1)
+    try:
+        ctx.set_pair_fusion(0)
+        sep, _ = m.infer(x, prio=ctx.S.PRIO_HIGH)
+        ctx.set_pair_fusion(1)
+        fused, _ = m.infer(x, prio=ctx.S.PRIO_HIGH)
+        names = [l.name.decode() for l in m.layers()]
+        assert np.array_equal(sep["logits"], fused["logits"]) and np.array_equal(sep["top1"], fused["top1"])
+        ref = omodels.resnet50_forward(md.tensors, x)
+        check_logits(fused["logits"], ref.logits, fused["top1"], "ResNet-50 b6, fused seams")
+        # intermediate activations read back through the fused path
+        ref = omodels.resnet50_forward(md.tensors, x, keep=True)
+        for lname, key in (("s1b1.c1", "s1b1.c1"), ("s1b1.out", "s1b1.c3"), ("s1b2.out", "s1b2.c3"), ("s2b0.c1", "s2b0.c1")):
+            got = m.read_activation(0, names.index(key), 6).astype(np.float64).reshape(ref.trace.acts[lname].shape)
+            check_kernel(got, ref.trace.acts[lname], f"layer {lname}", rel=2.0 ** -8, abs_rel=1e-2)
+    finally:
+        ctx.set_pair_fusion(200000)
+        m.free()
+
+
 @pytest.mark.parametrize("hw,batch", [(64, 5), (224, 2)])
 def test_mobilenet_v2(ctx, hw, batch):
     md = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2], hw=hw)
