@@ -1040,7 +1040,9 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         }
         if (t64 >= 256) return p.Kg >= 288 ? launch_dma_tile<128, 64, 32, 2, 2, 3>(p, mode, stream)
                                            : launch_dma_tile<128, 64, 32, 2, 2, 2>(p, mode, stream);
-        return launch_dma_tile<64, 64, 32, 2, 2, 2>(p, mode, stream);
+        // few, small tiles: nothing competes for LDS, and four slices in flight per workgroup instead of two shorten the
+        // latency chain of the reduction (ResNet-50 b32 0.96 -> 0.87 ms, b8 0.55 -> 0.53 ms; six are no better)
+        return launch_dma_tile<64, 64, 32, 2, 2, 4>(p, mode, stream);
     }
     if (p.Cout > 64 && tiles(128, 128) >= 512) return launch_tile<128, 128>(p, mode, staged, stream);
     if (tiles(128, 64) >= 512) return launch_tile<128, 64>(p, mode, staged, stream);
