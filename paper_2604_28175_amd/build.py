@@ -39,6 +39,11 @@ def build() -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     for o in objs:
         os.remove(o)
+    # the stand-alone ceilings program (MFMA, LDS-fed MFMA, streaming and host-link rates of the machine)
+    r = subprocess.run([HIPCC] + COMMON + [os.path.join(CSRC, "ceilings.hip"), "-o", os.path.join(HERE, "ceilings")],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on ceilings.hip:\n" + r.stderr)
     return LIB
 
 
