@@ -14,7 +14,11 @@ input already sits in device memory.  Prints ONE JSON line:
                 latter and the per-layer split (event pairs open gaps between launches, so they
                 are kept out of the pass `value` is taken from)
   cpu_baseline  the CPU oracle's ResNet-50 forward timed on this host on a bounded sample
-  by_batch      images/s at the other batch sizes of the workload (1, 8, 32), shorter runs
+  by_batch      the other batch sizes of the workload (1, 8, 32; the paper serves at batch <= 8, Section 5.1), shorter runs:
+                images/s, ms per step, TFLOP/s, and the fraction of the layer-wise roofline (sum over the layers of
+                max(flops / MFMA peak, bytes / HBM peak)) at that batch size
+  hbm_kernels   the bandwidth-bound kernels (depthwise convolution, pooling, softmax in MobileNetV2 b64; LayerNorm in the
+                encoder b64): algorithmic bytes / per-layer event time, as GB/s and as a fraction of the HBM peak
   two_instances images/s when the same K steps are issued alternately to two instances of the model on
                 the two compute streams (the paper's servers run several instances at once); not `value`
 """
@@ -36,12 +40,16 @@ MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
 
+TRAFFIC_FILE = "profiles/traffic_conv_igemm_resnet50_b128.json"
+
+
 def measured_traffic(batch):
-    """HBM bytes per step of the convolution launches from the committed hardware-counter runs, or None
-    when a kernel source has changed since they were taken (or the workload differs)."""
+    """HBM bytes per step of the convolution launches from the committed hardware-counter runs (TRAFFIC_FILE: this
+    process does not read counters), or None when a kernel source has changed since they were taken (or the workload
+    differs)."""
     import hashlib
     try:
-        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic_conv_igemm_resnet50_b128.json")))
+        rec = json.load(open(os.path.join(ROOT, TRAFFIC_FILE)))
         for src in rec["kernel_sources"]:
             if hashlib.sha256(open(os.path.join(ROOT, src["path"]), "rb").read()).hexdigest() != src["sha256"]:
                 return None
@@ -70,7 +78,7 @@ def colocation(ctx, md_resnet, blob_resnet, seconds):
     colocate.run(hp, hp_x, arrivals[:50], lp, lp_x, "hp_solo")            # warm-up
     h, _ = colocate.run(hp, hp_x, arrivals, lp, lp_x, "hp_solo")
     res["hp_solo"] = h.summary()
-    _, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "lp_solo", lp_solo_s=min(seconds, 1.0))
+    _, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "lp_solo", lp_solo_s=min(seconds, 3.0))
     res["lp_solo"] = l.summary()
     h, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "both")
     res["colocated"] = {"hp": h.summary(), "lp": l.summary()}
@@ -194,9 +202,11 @@ def main() -> int:
     ap.add_argument("--no-other-models", action="store_true", help="skip the throughput lines of the other served models (VGG-19, ViT-B/16, MobileNetV2, encoder)")
     ap.add_argument("--only-model", choices=("vgg19", "vit_b16", "mobilenet_v2", "encoder"), default=None,
                     help="time nothing but this model at batch 64 (for kernel profiles of the second workload set)")
-    ap.add_argument("--colocation-seconds", type=float, default=5.0,
+    ap.add_argument("--single-stream", action="store_true",
+                    help="keep the projection shortcuts on the main stream (kernel traces of such a run add up to the step time)")
+    ap.add_argument("--colocation-seconds", type=float, default=10.0,
                     help="length of each phase of the dual-priority co-location run (0 = skip)")
-    ap.add_argument("--serving-seconds", type=float, default=3.0,
+    ap.add_argument("--serving-seconds", type=float, default=2.0,
                     help="seconds per phase of the request-level serving run (0 = skip)")
     ap.add_argument("--serving-mixed-scale", type=float, default=1.0, help="multiplies the request rates of the four-model serving phase")
     ap.add_argument("--serving-hp-rate", type=float, default=4000.0, help="high-priority requests per second")
@@ -220,6 +230,8 @@ def main() -> int:
     md = synth.resnet50(seed)
     blob = synth.pack(md)
     ctx = strait.Context(device=0, n_hp=1, n_lp=1, n_copy=2)
+    if args.single_stream:
+        ctx.set_branch_streams(False)
     model = ctx.load(blob, max_batch=B, n_instances=1)
     x = synth.default_image_batch(md, B, seed + B)
     prio = strait.PRIO_HIGH
@@ -255,16 +267,56 @@ def main() -> int:
         omd, oblob = models_data(arch)
         om = ctx.load(oblob, max_batch=64, n_instances=1)
         if arch == synth.ARCH_ENCODER:
-            tokens, valid = synth.token_batch(omd, 64, 5)
+            tokens, valid = synth.token_batch(omd, 64, 5)      # (`valid` is also what the attention flops are counted with)
             om.copy_in(0, prio, tokens, valid)
         else:
             om.copy_in(0, prio, synth.default_image_batch(omd, 64, 5))
         om.sync(0, prio)
         odt, odev = timed(om, 64, steps, warmup)
-        macs = sum(l.macs_per_sample for l in om.layers())
+        olayers = om.layers()
+        # multiply-accumulates of the batch; attention counts what is computed: every query against the valid keys only
+        macs = 0.0
+        for l in olayers:
+            if l.kind == 5 and arch == synth.ARCH_ENCODER:
+                macs += float(l.macs_per_sample) * float(valid.sum()) / omd.hyper[4]
+            else:
+                macs += float(l.macs_per_sample) * 64
+        step_s = odev / steps * 1e-3
+        nbytes = sum(float(l.bytes_per_sample) * 64 + l.weight_bytes for l in olayers)
+        t_roof = sum(max(2.0 * l.macs_per_sample * 64 / (MFMA_F16_PEAK_TFLOPS * 1e12),
+                         (float(l.bytes_per_sample) * 64 + l.weight_bytes) / (HBM_PEAK_GBS * 1e9)) for l in olayers)
         res = {"batch": 64, "images_per_s": round(steps * 64 / odt, 1), "ms_per_step": round(odt / steps * 1e3, 4),
-               "tflops": round(2.0 * macs * 64 / (odev / steps * 1e-3) / 1e12, 1),
-               "frac_of_mfma_peak": round(2.0 * macs * 64 / (odev / steps * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+               "tflops": round(2.0 * macs / step_s / 1e12, 1),
+               "frac_of_mfma_peak": round(2.0 * macs / step_s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+               "algorithmic_gbs": round(nbytes / step_s / 1e9, 1),
+               "frac_of_hbm_peak": round(nbytes / step_s / 1e9 / HBM_PEAK_GBS, 4),
+               "bound": "hbm" if nbytes / (HBM_PEAK_GBS * 1e9) > 2.0 * macs / (MFMA_F16_PEAK_TFLOPS * 1e12) else "mfma",
+               "layerwise_roofline_ms": round(t_roof * 1e3, 4), "frac_of_layerwise_roofline": round(t_roof / step_s, 4)}
+        if arch in (synth.ARCH_MOBILENETV2, synth.ARCH_ENCODER):
+            # the bandwidth-bound kernels one by one: an event pair around every layer (a few microseconds of gap per
+            # layer are booked to the kernels this way, so these are lower bounds of the kernels' own rates)
+            lms = np.zeros(len(olayers))
+            for _ in range(steps):
+                lms += om.run_timed(0, prio, 64)
+            lms /= steps
+            kinds = {1: "depthwise_conv3x3", 2: "pooling", 3: "softmax", 4: "layernorm"}
+            hk = {}
+            for i, l in enumerate(olayers):
+                if l.kind in kinds and l.bytes_per_sample > 0:
+                    e = hk.setdefault(kinds[l.kind], {"launches": 0, "bytes": 0.0, "ms": 0.0, "best_gbs": 0.0})
+                    by = float(l.bytes_per_sample) * 64 + l.weight_bytes
+                    e["launches"] += 1
+                    e["bytes"] += by
+                    e["ms"] += float(lms[i])
+                    e["best_gbs"] = max(e["best_gbs"], by / (float(lms[i]) * 1e-3) / 1e9)
+            for e in hk.values():
+                e["gbs"] = round(e["bytes"] / (e["ms"] * 1e-3) / 1e9, 1)
+                e["frac_of_hbm_peak"] = round(e["gbs"] / HBM_PEAK_GBS, 4)
+                e["best_layer_gbs"] = round(e.pop("best_gbs"), 1)
+                e["best_layer_frac_of_hbm_peak"] = round(e["best_layer_gbs"] / HBM_PEAK_GBS, 4)
+                e["ms"] = round(e["ms"], 4)
+                e["bytes"] = int(e["bytes"])
+            res["hbm_kernels"] = hk
         om.free()
         return res
 
@@ -341,6 +393,7 @@ def main() -> int:
                    "batch": B, "priority": "high"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic(B),
+                     "traffic_source": TRAFFIC_FILE + " (rocprofv3 FETCH_SIZE and WRITE_SIZE runs of this command, committed; null when a kernel source has changed since)",
                      "algorithmic_bytes_per_step": sum(float(layers[i].bytes_per_sample) * B + layers[i].weight_bytes for i in conv),
                      "kernel": "conv_igemm_dma_kernel (all tile shapes), conv3x3_patch_kernel and stem_pool_kernel: the 54 MFMA launches of a step (53 convolutions, the first fused with the pooling behind it, and the classifier)",
                      "flops_per_step": conv_flops, "kernel_ms_per_step": round(conv_ms, 4),
@@ -352,16 +405,27 @@ def main() -> int:
                                      "ms": round(v[2], 4)} for k, v in cls.items()}},
     }
 
+    def batch_line(b, images_per_s, step_ms):
+        """Throughput of one batch size against its own layer-wise roofline (weights are read once per step whatever
+        the batch, so small batches are weight-bound)."""
+        fl = sum(2.0 * layers[i].macs_per_sample * b for i in conv)
+        roof = sum(max(2.0 * l.macs_per_sample * b / (MFMA_F16_PEAK_TFLOPS * 1e12),
+                       (float(l.bytes_per_sample) * b + l.weight_bytes) / (HBM_PEAK_GBS * 1e9)) for l in layers)
+        return {"images_per_s": round(images_per_s, 1), "ms_per_step": round(step_ms, 4),
+                "tflops": round(fl / (step_ms * 1e-3) / 1e12, 1), "frac_of_mfma_peak": round(fl / (step_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                "layerwise_roofline_ms": round(roof * 1e3, 4), "frac_of_layerwise_roofline": round(roof * 1e3 / step_ms, 4)}
+
     if not args.no_by_batch:
-        by = {str(B): round(value, 1)}
+        by = {str(B): batch_line(B, value, dev_ms / K)}
         for b in (32, 8, 1):
             if b >= B:
                 continue
             xb = synth.default_image_batch(md, b, seed + b)
             model.copy_in(0, prio, xb)
             model.sync(0, prio)
-            d, _ = timed(model, b, max(20, K), max(5, W))
-            by[str(b)] = round(max(20, K) * b / d, 1)
+            kb = max(20, K)
+            d, dms = timed(model, b, kb, max(5, W))
+            by[str(b)] = batch_line(b, kb * b / d, dms / kb)
         out["by_batch"] = by
 
     model.free()
@@ -437,6 +501,10 @@ def main() -> int:
         # the paper's other image classifiers by shape (Table 1): VGG-19 (all 3x3 convolutions, MFMA-bound) and
         # ViT-B/16 (197 tokens), batch 64, input resident, same timing as the headline value
         out["other_models"] = {name: other_model(arch) for name, arch in others.items()}
+        out["hbm_kernels"] = {"mobilenet_v2_b64": out["other_models"]["mobilenet_v2"].pop("hbm_kernels"),
+                              "encoder_b64": out["other_models"]["encoder"].pop("hbm_kernels"),
+                              "peak_gbs": HBM_PEAK_GBS,
+                              "note": "algorithmic bytes (input + output + parameters once) over per-layer event time"}
 
     if args.colocation_seconds > 0:
         out["colocation"] = colocation(ctx, md, blob, args.colocation_seconds)
