@@ -320,6 +320,13 @@ def main() -> int:
         om.free()
         return res
 
+    if args.copy_calibration_mb > 0:
+        src = torch.empty(args.copy_calibration_mb << 20, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # (for the encoder an "image" is a 128-token sequence with a seeded valid length)
     others = {"vgg19": synth.ARCH_VGG19, "vit_b16": synth.ARCH_VIT, "mobilenet_v2": synth.ARCH_MOBILENETV2, "encoder": synth.ARCH_ENCODER}
     if args.only_model:
@@ -328,13 +335,6 @@ def main() -> int:
         model.free()
         ctx.close()
         return 0
-
-    if args.copy_calibration_mb > 0:
-        src = torch.empty(args.copy_calibration_mb << 20, dtype=torch.uint8, device="cuda").zero_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     dt, dev_ms = timed(model, B, K, W)
     value = K * B / dt

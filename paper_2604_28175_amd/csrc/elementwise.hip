@@ -118,6 +118,15 @@ int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, in
     return 0;
 }
 
+// Hardware workgroup id b runs on XCD b mod 8, each XCD with an L2 of its own.  This gives every XCD a contiguous
+// range of logical block numbers instead, so that blocks which share input rows (vertically adjacent row tiles of a
+// stencil) fetch them through one L2 rather than through several.
+__device__ __forceinline__ unsigned xcd_contiguous_block() {
+    const unsigned nb = gridDim.x, b = blockIdx.x;
+    const unsigned per = nb >> 3, rem = nb & 7, xcd = b & 7, idx = b >> 3;
+    return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+}
+
 // ------------------------------------------------------------------------------------------
 // depthwise 3x3, pad 1, stride 1 or 2, fused bias + activation.
 // A thread owns 8 channels (16 bytes) of TW consecutive output pixels of one output row.  For each
@@ -134,7 +143,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_kernel(const half_t* __restrict
     const unsigned C8 = (unsigned)C >> 3;
     const unsigned QT = (unsigned)(Q + TW - 1) / TW;
     const unsigned long long total = (unsigned long long)N * P * QT * C8;
-    const unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long i = (unsigned long long)xcd_contiguous_block() * 256 + threadIdx.x;
     if (i >= total) return;
     const unsigned c8 = (unsigned)(i % C8);
     unsigned t = (unsigned)(i / C8);
@@ -213,7 +222,7 @@ __global__ void __launch_bounds__(256) dwconv3x3_s1_cols_kernel(const half_t* __
     const unsigned C8 = (unsigned)C >> 3;
     const unsigned PT = (unsigned)(H + TH - 1) / TH;
     const unsigned long long total = (unsigned long long)N * PT * W * C8;
-    const unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long i = (unsigned long long)xcd_contiguous_block() * 256 + threadIdx.x;
     if (i >= total) return;
     const unsigned c8 = (unsigned)(i % C8);
     unsigned t = (unsigned)(i / C8);
