@@ -86,9 +86,17 @@ def colocation(ctx, md_resnet, blob_resnet, seconds):
     h, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "both")
     res["colocated_no_wave_priority"] = {"hp": h.summary(), "lp": l.summary()}
     ctx.set_wave_priority(True)
-    solo, co = res["hp_solo"]["latency_ms"], res["colocated"]["hp"]["latency_ms"]
+    # the low-priority batches issued in segments of four layers that yield while a high-priority batch is in flight
+    ctx.set_lp_yield(4)
+    h, l = colocate.run(hp, hp_x, arrivals, lp, lp_x, "both")
+    res["colocated_lp_yield_4"] = {"hp": h.summary(), "lp": l.summary()}
+    ctx.set_lp_yield(0)
+    solo, co, coy = res["hp_solo"]["latency_ms"], res["colocated"]["hp"]["latency_ms"], res["colocated_lp_yield_4"]["hp"]["latency_ms"]
     res["hp_p99_colocated_over_solo"] = round(co["p99"] / solo["p99"], 3)
     res["hp_p50_colocated_over_solo"] = round(co["p50"] / solo["p50"], 3)
+    res["hp_p99_colocated_over_solo_lp_yield_4"] = round(coy["p99"] / solo["p99"], 3)
+    res["hp_p50_colocated_over_solo_lp_yield_4"] = round(coy["p50"] / solo["p50"], 3)
+    res["lp_images_per_s_lp_yield_4_over_default"] = round(res["colocated_lp_yield_4"]["lp"]["images_per_s"] / res["colocated"]["lp"]["images_per_s"], 3)
     hp.free()
     lp.free()
     return res

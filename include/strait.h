@@ -139,6 +139,15 @@ strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
  * tiles, which pays for loading the weights into LDS once per workgroup); 0 = always two launches.  Results are the
  * same bit for bit. */
 strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
+/* Yielding of low-priority batches.  The paper separates the two levels by stream priority, "a hardware-level hint"
+ * without preemption (Section 3.1), and bounds what low-priority work may take of a GPU (Section 3.3).  Where stream
+ * priorities are not available this is the library's own lever: with layers_per_segment > 0 the kernel sequence of a
+ * low-priority batch is enqueued in segments of that many layers, at most two segments ahead of the GPU, and no
+ * further segment is enqueued while a high-priority batch is in flight on this context (for at most 5 ms per segment).
+ * A high-priority batch then shares the GPU with at most the rest of two short segments.  strait_submit stays
+ * non-blocking (the stream's completion thread does the issuing); results do not change.  0 (default) = the whole
+ * sequence is enqueued at once. */
+strait_status strait_ctx_set_lp_yield(strait_ctx* ctx, int32_t layers_per_segment);
 /* Whether a plan's independent branches (the projection shortcut of a residual stage's first block) run on the
  * instance's side stream beside the main sequence (default on).  Off keeps every launch on the one compute stream, in
  * plan order: kernel traces of such a run add up to the step time. */

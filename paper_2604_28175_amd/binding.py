@@ -70,6 +70,7 @@ _SIGS = {
     "strait_ctx_set_graphs": (_i32, [_vp, _i32]),
     "strait_ctx_set_h2d_kernel_limit": (_i32, [_vp, C.c_int64]),
     "strait_ctx_set_branch_streams": (_i32, [_vp, _i32]),
+    "strait_ctx_set_lp_yield": (_i32, [_vp, _i32]),
     "strait_ctx_set_pair_fusion": (_i32, [_vp, _i64]),
     "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
     "strait_model_free": (_i32, [_vp]),
@@ -187,6 +188,9 @@ class Context:
 
     def set_pair_fusion(self, min_pixels: int):
         _check(lib.strait_ctx_set_pair_fusion(self.handle, int(min_pixels)))
+
+    def set_lp_yield(self, layers_per_segment: int):
+        _check(lib.strait_ctx_set_lp_yield(self.handle, int(layers_per_segment)))
 
     def set_branch_streams(self, enabled: bool):
         _check(lib.strait_ctx_set_branch_streams(self.handle, 1 if enabled else 0))

@@ -37,6 +37,39 @@ static int64_t now_ns() {
     return (int64_t)ts.tv_sec * 1000000000LL + ts.tv_nsec;
 }
 
+// A yielding low-priority batch (strait_ctx_set_lp_yield): its kernel sequence is enqueued by the stream's worker thread
+// in segments of a few layers, at most two segments in flight, and before each further segment the thread waits while a
+// high-priority batch is in flight on the GPU (at most kMaxYieldNs per segment, so that the wait always ends).  What
+// the GPU runs beside a high-priority batch is then at most the rest of two short segments instead of a whole batch.
+static const int64_t kMaxYieldNs = 5000000;
+static int issue_in_segments(Context* ctx, StreamWorker* w, Ticket* t) {
+    Model& m = *t->model;
+    Instance& in = m.inst[t->instance];
+    hipStream_t s = w->stream;
+    const int n = (int)m.ops.size();
+    int seg;
+    { std::lock_guard<std::mutex> lk(ctx->mu); seg = ctx->lp_yield_layers > 0 ? ctx->lp_yield_layers : n; }
+    if (hipStreamWaitEvent(s, in.ev_h2d1, 0) != hipSuccess || hipEventRecord(in.ev_k0, s) != hipSuccess) return STRAIT_E_HIP;
+    int k = 0;
+    for (int first = 0; first < n; first += seg, ++k) {
+        if (k >= 1) {
+            const int64_t t0 = now_ns();
+            while (ctx->hp_in_flight.load(std::memory_order_acquire) > 0 && now_ns() - t0 < kMaxYieldNs) {
+                timespec ts{0, 20000};
+                nanosleep(&ts, nullptr);
+            }
+        }
+        const int last = first + seg - 1 < n - 1 ? first + seg - 1 : n - 1;
+        if (run_plan(m, in, t->batch, s, t->hp, last, false, first)) return STRAIT_E_HIP;
+        if (hipEventRecord(in.ev_seg[k & 1], s) != hipSuccess) return STRAIT_E_HIP;
+        if (k >= 1 && hipEventSynchronize(in.ev_seg[(k - 1) & 1]) != hipSuccess) return STRAIT_E_HIP;   // one segment of look-ahead
+    }
+    if (hipEventRecord(in.ev_k1, s) != hipSuccess) return STRAIT_E_HIP;
+    if (launch_copy_mapped(in.dev_out, in.pinned_out_dev, m.out_bytes(t->batch), t->hp, s)) return STRAIT_E_HIP;
+    if (hipEventRecord(in.ev_done, s) != hipSuccess) return STRAIT_E_HIP;
+    return 0;
+}
+
 static void worker_loop(Context* ctx, StreamWorker* w) {
     (void)hipSetDevice(ctx->device);
     for (;;) {
@@ -49,11 +82,13 @@ static void worker_loop(Context* ctx, StreamWorker* w) {
             w->q.pop_front();
         }
         Instance& in = t->model->inst[t->instance];
-        hipError_t e = hipEventSynchronize(in.ev_done);
-        const int64_t done = now_ns();
         int status = 0;
+        if (t->deferred) status = issue_in_segments(ctx, w, t);
+        hipError_t e = status ? hipSuccess : hipEventSynchronize(in.ev_done);
+        const int64_t done = now_ns();
+        if (t->prio == STRAIT_PRIO_HIGH) ctx->hp_in_flight.fetch_sub(1, std::memory_order_acq_rel);
         if (e != hipSuccess) status = STRAIT_E_HIP;
-        else {
+        else if (!status) {
             memcpy(t->host_out, in.pinned_out, t->model->out_bytes(t->batch));
             float ms = 0.f;
             if (hipEventElapsedTime(&ms, in.ev_h2d0, in.ev_h2d1) == hipSuccess) t->rec.h2d_ms = ms;
@@ -143,6 +178,13 @@ strait_status strait_ctx_set_pair_fusion(strait_ctx* c, int64_t min_pixels) {
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_lp_yield(strait_ctx* c, int32_t layers_per_segment) {
+    if (!c || layers_per_segment < 0) { set_error("ctx_set_lp_yield: null context or negative segment length"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->lp_yield_layers = layers_per_segment;
+    return STRAIT_OK;
+}
+
 strait_status strait_ctx_set_branch_streams(strait_ctx* c, int32_t enabled) {
     if (!c) { set_error("ctx_set_branch_streams: null"); return STRAIT_E_INVALID; }
     std::lock_guard<std::mutex> lk(c->mu);
@@ -189,7 +231,7 @@ static void free_instance(Instance& in) {
     if (in.splitk_ws) (void)hipFree(in.splitk_ws);
     for (void* b : in.bufs) if (b) (void)hipFree(b);
     if (in.side) { (void)hipStreamSynchronize(in.side); (void)hipStreamDestroy(in.side); }
-    hipEvent_t evs[7] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done, in.ev_fork, in.ev_join};
+    hipEvent_t evs[9] = {in.ev_h2d0, in.ev_h2d1, in.ev_k0, in.ev_k1, in.ev_done, in.ev_fork, in.ev_join, in.ev_seg[0], in.ev_seg[1]};
     for (hipEvent_t e : evs) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : in.layer_ev) if (e) (void)hipEventDestroy(e);
     for (auto& kv : in.graphs) (void)hipGraphExecDestroy(kv.second);
@@ -233,6 +275,8 @@ strait_status strait_model_load(strait_ctx* c, const strait_model_desc* d, strai
         ok = ok && hipEventCreate(&in.ev_h2d0) == hipSuccess && hipEventCreate(&in.ev_h2d1) == hipSuccess &&
              hipEventCreate(&in.ev_k0) == hipSuccess && hipEventCreate(&in.ev_k1) == hipSuccess &&
              hipEventCreate(&in.ev_done) == hipSuccess &&
+             hipEventCreateWithFlags(&in.ev_seg[0], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&in.ev_seg[1], hipEventDisableTiming) == hipSuccess &&
              hipStreamCreateWithFlags(&in.side, hipStreamNonBlocking) == hipSuccess &&      // default priority
              hipEventCreateWithFlags(&in.ev_fork, hipEventDisableTiming) == hipSuccess &&
              hipEventCreateWithFlags(&in.ev_join, hipEventDisableTiming) == hipSuccess;
@@ -405,7 +449,19 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
     t->model = m; t->instance = idx; t->prio = prio; t->batch = batch; t->host_out = host_out;
     t->rec.model_id = m->id; t->rec.priority = prio; t->rec.batch = batch; t->rec.instance = idx;
     t->rec.t_enqueue_ns = t_enq;
-    {
+    bool yielding;
+    { std::lock_guard<std::mutex> lk(c->mu); yielding = prio == STRAIT_PRIO_LOW && c->lp_yield_layers > 0; }
+    t->hp = hp_flag(c, prio);
+    if (prio == STRAIT_PRIO_HIGH) c->hp_in_flight.fetch_add(1, std::memory_order_acq_rel);
+    if (yielding) {
+        // the stream's worker thread enqueues the kernels, segment by segment (issue_in_segments)
+        t->deferred = true;
+        if (!rc) {
+            t->rec.t_issued_ns = now_ns();
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->workers[widx]->q.push_back(t);
+        }
+    } else {
         std::lock_guard<std::mutex> slk(c->compute_mu[widx]);
         if (!rc) rc = hipStreamWaitEvent(s, in.ev_h2d1, 0) == hipSuccess ? 0 : STRAIT_E_HIP;
         if (!rc) rc = hipEventRecord(in.ev_k0, s) == hipSuccess ? 0 : STRAIT_E_HIP;
@@ -420,6 +476,7 @@ strait_status strait_submit(strait_model* m, strait_priority prio, int32_t batch
         }
     }
     if (rc) {
+        if (prio == STRAIT_PRIO_HIGH) c->hp_in_flight.fetch_sub(1, std::memory_order_acq_rel);
         if (rc == STRAIT_E_HIP && !strait::last_error()[0]) set_error("submit: a HIP call failed");
         (void)hipStreamSynchronize(s);
         (void)hipStreamSynchronize(cs);

@@ -857,15 +857,16 @@ static void* slot_ptr(Model& m, Instance& in, int slot, int ref, int batch) {
     return nullptr;
 }
 
-int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed) {
+int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed, int first_layer) {
     const int n = (int)m.ops.size();
     if (last_layer < 0 || last_layer >= n) last_layer = n - 1;
     // Per-layer timing and prefix runs keep everything on the one stream (their events bracket single launches).
-    const bool branches = !timed && last_layer == n - 1 && in.side != nullptr && m.ctx->branch_streams;
+    if (first_layer < 0 || first_layer > last_layer) first_layer = 0;
+    const bool branches = !timed && first_layer == 0 && last_layer == n - 1 && in.side != nullptr && m.ctx->branch_streams;
     bool forked = false;
     hipStream_t main_stream = stream;
     int fused_away = -1;                                // op already computed by the pair launch of an earlier op
-    for (int i = 0; i <= last_layer; ++i) {
+    for (int i = first_layer; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
         stream = main_stream;
         if (i == fused_away) {

@@ -71,6 +71,7 @@ struct Instance {
     float* splitk_ws = nullptr;        // fp32 slabs of split-K convolutions (small batches)
     std::vector<void*> bufs;
     hipEvent_t ev_h2d0 = nullptr, ev_h2d1 = nullptr, ev_k0 = nullptr, ev_k1 = nullptr, ev_done = nullptr;
+    hipEvent_t ev_seg[2] = {nullptr, nullptr};   // ends of the two plan segments a yielding low-priority batch has in flight
     hipStream_t side = nullptr;        // default priority, non-blocking: carries branches that do not depend on each other
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> layer_ev;
@@ -113,6 +114,8 @@ struct Ticket {
     strait_record rec{};
     bool done = false;
     int status = 0;
+    bool deferred = false;             // kernels not enqueued yet: the stream's worker issues them segment by segment
+    int hp = 0;                        // wave-priority flag its kernels are launched with
 };
 
 struct StreamWorker {
@@ -135,6 +138,8 @@ struct Context {
     bool wave_priority = true;
     bool use_graphs = false;
     long long pair_min_pixels = 200000;     // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
+    int lp_yield_layers = 0;                // > 0: low-priority batches are issued in segments of this many layers and yield between them
+    std::atomic<int> hp_in_flight{0};       // high-priority batches submitted and not yet complete
     bool branch_streams = true;             // independent branches of a plan go to the instance's side stream
     size_t h2d_kernel_limit = 8u << 20;   // inputs up to this size go in by a copy kernel, larger ones by hipMemcpyAsync
     unsigned n_hp_sub = 0, n_lp_sub = 0, n_copy_sub = 0;
@@ -142,6 +147,7 @@ struct Context {
 };
 
 int build_plan(Model& m, const void* blob, size_t bytes);
-int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed);
+// Enqueues layers first_layer..last_layer (last_layer < 0: up to the end) of the plan for `batch` samples on `stream`.
+int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int last_layer, bool timed, int first_layer = 0);
 
 }  // namespace strait

@@ -119,3 +119,33 @@ def test_open_loop_colocation_short(env):
     out2, _ = hp.infer(hp_x[0], prio=S.PRIO_HIGH)
     ctx.set_wave_priority(True)
     assert np.array_equal(out["logits"], out2["logits"])
+
+
+def test_yielding_low_priority_batches_give_the_same_results(env):
+    """Low-priority batches issued in segments that yield to high-priority batches (strait_ctx_set_lp_yield): the same
+    outputs bit for bit, whatever the segment length, alone and with high-priority requests arriving meanwhile; as a
+    low-priority model a ResNet-50 as well (fused seams and side-stream branches are cut by segment ends)."""
+    S, colocate, ctx, md_hp, hp, md_lp, lp = env
+    x_lp = synth.default_image_batch(md_lp, 64, 31)
+    x_hp = synth.default_image_batch(md_hp, 8, 32)
+    ref_lp, _ = lp.infer(x_lp, prio=S.PRIO_LOW)
+    ref_hp_as_lp, _ = hp.infer(x_hp, prio=S.PRIO_LOW)
+    try:
+        for seg in (1, 3, 7, 1000):
+            ctx.set_lp_yield(seg)
+            out, rec = lp.infer(x_lp, prio=S.PRIO_LOW)
+            assert np.array_equal(out["logits"], ref_lp["logits"]) and np.array_equal(out["top1"], ref_lp["top1"])
+            assert rec.kernel_ms > 0 and rec.h2d_ms > 0
+            out, _ = hp.infer(x_hp, prio=S.PRIO_LOW)
+            assert np.array_equal(out["logits"], ref_hp_as_lp["logits"])
+        ctx.set_lp_yield(4)
+        arr = synth.poisson_arrivals_ns(synth.SEEDS["colocation"], 400.0, 0.4)
+        h, l = colocate.run(hp, [x_hp], arr, lp, [x_lp], "both")
+        assert h.dropped == 0 and len(h.latency_ms) == len(arr) and l.requests >= 1
+        print("with yielding: hp", h.summary()["latency_ms"], "lp images/s", l.summary()["images_per_s"])
+        out, _ = lp.infer(x_lp, prio=S.PRIO_LOW)
+        assert np.array_equal(out["logits"], ref_lp["logits"])
+        out, _ = hp.infer(x_hp, prio=S.PRIO_HIGH)
+        assert np.array_equal(out["logits"], ref_hp_as_lp["logits"])
+    finally:
+        ctx.set_lp_yield(0)
