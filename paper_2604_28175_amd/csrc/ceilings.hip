@@ -8,6 +8,8 @@
 //   3. streaming kernels: fill, read-only reduction, copy (16 bytes per lane, grid-stride), at a size that fits the
 //      256 MB memory-side cache and at sizes that do not.
 //   4. pinned host-to-device hipMemcpyAsync.
+//   5. the cadence of dependent launches on one stream: an empty kernel, and a kernel whose single workgroup makes one
+//      round trip to memory (load, then a dependent store), which is what the shortest possible layer costs.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -105,6 +107,9 @@ __global__ void __launch_bounds__(256) stream_read(const uint4* src, unsigned* o
     if (acc == 0x12345678u) out[0] = acc;             // practically never: keeps the loads alive
 }
 
+__global__ void empty_kernel() {}
+__global__ void __launch_bounds__(256) round_trip_kernel(const float* src, float* dst) { dst[threadIdx.x] = src[threadIdx.x] + 1.f; }
+
 int main() {
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0));
@@ -186,6 +191,22 @@ int main() {
         CK(hipEventSynchronize(e1));
         CK(hipEventElapsedTime(&ms, e0, e1));
         printf("   %4zu MiB: %5.1f GB/s (%.3f ms per copy)\n", mb, (double)(mb << 20) * 3 / (ms * 1e-3) / 1e9, ms / 3);
+    }
+
+    printf("\n5. dependent launches on one stream (1000 in a row, events around them)\n");
+    for (int kind = 0; kind < 3; ++kind) {
+        for (int rep = 0; rep < 2; ++rep) {
+            CK(hipEventRecord(e0, st));
+            for (int i = 0; i < 1000; ++i) {
+                if (kind == 0) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, st);
+                else if (kind == 1) hipLaunchKernelGGL(round_trip_kernel, dim3(1), dim3(256), 0, st, (const float*)a + (i & 1) * 256, (float*)a + ((i + 1) & 1) * 256);
+                else hipLaunchKernelGGL(round_trip_kernel, dim3(256), dim3(256), 0, st, (const float*)a + (i & 1) * 256, (float*)a + ((i + 1) & 1) * 256);
+            }
+            CK(hipEventRecord(e1, st));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        printf("   %-58s %5.2f us per launch\n", kind == 0 ? "empty kernel, one wavefront:" : kind == 1 ? "load + dependent store, one workgroup:" : "load + dependent store, 256 workgroups (same addresses):", ms);
     }
     return 0;
 }
