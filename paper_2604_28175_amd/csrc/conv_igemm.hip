@@ -902,8 +902,8 @@ static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
     const int wp = sw + (p.W == sw ? 1 : 2);
     const long long mv = (long long)(p.M / p.PQ) * (p.W / sw) * (p.H + 1) * wp;
     // with fewer tiles than half the compute units the generic kernel, which may split its reduction, is the faster one
-    // (ResNet-50 batch 8, 28 x 28 x 128: 12.2 against 10.1 us; batch 32: 12.7 against 17.1 us)
-    if ((mv + 255) / 256 * ((p.Cout + 127) / 128) < 128) return -1;
+    // (ResNet-50 batch 8, 28 x 28 x 128, 53 tiles: 12.2 against 9.2 us; batch 32, 210 tiles: 12.7 against 17.1 us)
+    if ((p.Cout % 128 == 0 ? (mv + 127) / 128 * (p.Cout / 128) : (mv + 255) / 256 * (p.Cout / 64)) < 128) return -1;
     if (mv >= (1LL << 24) - 4096) return -1;           // the kernel's index arithmetic is exact below 2^24
     auto per_wave = [&](int bm, int nw) { return ((bm + 2 * wp + 2 + 15) / 16 + nw - 1) / nw; };
     if (p.Cout % 128 == 0) {
@@ -1025,6 +1025,9 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
             while (ks > 1 && ks * (long long)p.M * p.Cout * 4 > (long long)p.ws_bytes) --ks;
             if (ks > 1) {
                 p.ksplit = (int)ks;
+                // dense products with four or more 32-wide slices per workgroup take them 64 wide: half the barriers and
+                // round trips of the chain (1024 -> 256 at 14 x 14, batch 1: 10.2 -> 7.9 us); gathered 3x3 slices do not gain
+                if (mode == MODE_1X1 && p.Kg % 64 == 0 && nk / ks >= 4) return launch_dma_tile<64, 64, 64, 2, 2, 3>(p, mode, stream);
                 return launch_dma_tile<64, 64, 32, 2, 2, 3>(p, mode, stream);
             }
         }
@@ -1057,6 +1060,7 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
                                            : launch_dma_tile<128, 64, 32, 2, 2, 2>(p, mode, stream);
         // few, small tiles: nothing competes for LDS, and four slices in flight per workgroup instead of two shorten the
         // latency chain of the reduction (ResNet-50 b32 0.96 -> 0.87 ms, b8 0.55 -> 0.53 ms; six are no better)
+        if (bk64) return launch_dma_tile<64, 64, 64, 2, 2, 3>(p, mode, stream);      // the same bytes in flight in half the steps
         return launch_dma_tile<64, 64, 32, 2, 2, 4>(p, mode, stream);
     }
     if (p.Cout > 64 && tiles(128, 128) >= 512) return launch_tile<128, 128>(p, mode, staged, stream);
