@@ -137,7 +137,7 @@ struct Context {
     bool stop = false;
     bool wave_priority = true;
     bool use_graphs = false;
-    long long pair_min_pixels = 200000;     // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
+    long long pair_min_pixels = 300000;     // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
     int lp_yield_layers = 0;                // > 0: low-priority batches are issued in segments of this many layers and yield between them
     std::atomic<int> hp_in_flight{0};       // high-priority batches submitted and not yet complete
     bool branch_streams = true;             // independent branches of a plan go to the instance's side stream
