@@ -139,6 +139,13 @@ strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
  * layers still fits the GPU's memory-side cache and two launches are as fast: batch 64 1.32 ms either way, batch 128
  * 2.29 -> 2.20 ms); 0 = always two launches.  Results are the same bit for bit. */
 strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
+/* The same threshold for a pair in the first block of a residual stage whose projection shortcut has stride 1 (ResNet-50's
+ * first stage): there the one launch (strait_k_pointwise_pair_proj) also replaces the projection's launch, and neither the
+ * projected tensor nor its read-back exists.  Default 3000 pixels (ResNet-50 from batch 1 on: batch 128 2.094 -> 2.014 ms,
+ * batch 16 0.610 -> 0.555 ms, batch 1 0.452 -> 0.449 ms).  Not bit-identical to separate launches: the sum of the two
+ * products is rounded to fp16 once instead of the projection first.  With strait_ctx_set_pair_fusion(ctx, 0) no pair
+ * is fused, this kind included. */
+strait_status strait_ctx_set_proj_fusion(strait_ctx* ctx, int64_t min_pixels);
 /* Yielding of low-priority batches.  The paper separates the two levels by stream priority, "a hardware-level hint"
  * without preemption (Section 3.1), and bounds what low-priority work may take of a GPU (Section 3.3).  Where stream
  * priorities are not available this is the library's own lever: with layers_per_segment > 0 the kernel sequence of a
@@ -250,6 +257,17 @@ strait_status strait_k_gemm_noalloc(void* stream, const void* x, const void* w, 
 strait_status strait_k_pointwise_pair(void* stream, const void* x, const void* w3, const float* b3, const void* res, void* y,
                                       const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t N1, int32_t N2,
                                       int32_t act1, int32_t act2, int32_t hp);
+/* The same pair where the first block's shortcut is a 1x1 projection of a second tensor (the first block of a residual
+ * stage; Section 3.2 step (2)): the projection joins the first product's reduction instead of being written out and read
+ * back as a residual,
+ *     y[m, 0:N1] = act1([x[m, 0:K1] | x2[m, 0:K2]] w3^T + b3);     z[m, 0:N2] = act2(y[m, 0:N1] w1^T + b1)
+ * x [M][K1], x2 [M][K2], w3 [N1][K1 + K2] (the closing convolution's weights beside the projection's; b3 the sum of the
+ * two biases), y [M][N1], w1 [N2][N1], z [M][N2], dense fp16 device memory.  K1 = K2 = 64, N1 = 256, N2 = 64 (E_SHAPE
+ * otherwise); x2 NULL is E_INVALID.  The sum is rounded to fp16 once, where two launches round the projection first.
+ * z must not overlap x or x2. */
+strait_status strait_k_pointwise_pair_proj(void* stream, const void* x, const void* x2, const void* w3, const float* b3, void* y,
+                                           const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t K2, int32_t N1,
+                                           int32_t N2, int32_t act1, int32_t act2, int32_t hp);
 /* Depthwise 3x3: y[n,p,q,c] = act(bias[c] + sum_{r,s} x[..,c] * w[r][s][c]); w fp16 [3][3][C]; C % 8 == 0. */
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,

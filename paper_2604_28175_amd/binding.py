@@ -72,6 +72,7 @@ _SIGS = {
     "strait_ctx_set_branch_streams": (_i32, [_vp, _i32]),
     "strait_ctx_set_lp_yield": (_i32, [_vp, _i32]),
     "strait_ctx_set_pair_fusion": (_i32, [_vp, _i64]),
+    "strait_ctx_set_proj_fusion": (_i32, [_vp, _i64]),
     "strait_model_load": (_i32, [_vp, C.POINTER(ModelDesc), C.POINTER(_vp)]),
     "strait_model_free": (_i32, [_vp]),
     "strait_model_io": (_i32, [_vp, _i32, C.POINTER(_sz), C.POINTER(_sz)]),
@@ -91,6 +92,7 @@ _SIGS = {
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_pointwise_pair": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
+    "strait_k_pointwise_pair_proj": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_maxpool3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32]),
     "strait_k_stem_pool": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _i32]),
@@ -188,6 +190,9 @@ class Context:
 
     def set_pair_fusion(self, min_pixels: int):
         _check(lib.strait_ctx_set_pair_fusion(self.handle, int(min_pixels)))
+
+    def set_proj_fusion(self, min_pixels: int):
+        _check(lib.strait_ctx_set_proj_fusion(self.handle, int(min_pixels)))
 
     def set_lp_yield(self, layers_per_segment: int):
         _check(lib.strait_ctx_set_lp_yield(self.handle, int(layers_per_segment)))
@@ -382,6 +387,18 @@ def k_pointwise_pair(x, w3, b3, res, w1, b1, act1=ACT_RELU, act2=ACT_RELU, hp=0,
     z = torch.empty((m, n2), dtype=torch.float16, device=x.device)
     _check(lib.strait_k_pointwise_pair(_stream(stream), _dev(x), _dev(w3), _dev(b3), _dev(res), _dev(y), _dev(w1), _dev(b1),
                                        _dev(z), m, k1, n1, n2, act1, act2, hp))
+    return y, z
+
+
+def k_pointwise_pair_proj(x, x2, w3, b3, w1, b1, act1=ACT_RELU, act2=ACT_RELU, hp=0, stream=None):
+    import torch
+    m, k1 = x.shape
+    k2 = x2.shape[1] if x2 is not None else 0
+    n1, n2 = w3.shape[0], w1.shape[0]
+    y = torch.empty((m, n1), dtype=torch.float16, device=x.device)
+    z = torch.empty((m, n2), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_pointwise_pair_proj(_stream(stream), _dev(x), _dev(x2), _dev(w3), _dev(b3), _dev(y), _dev(w1), _dev(b1),
+                                            _dev(z), m, k1, k2, n1, n2, act1, act2, hp))
     return y, z
 
 

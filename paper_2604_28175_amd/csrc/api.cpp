@@ -178,6 +178,13 @@ strait_status strait_ctx_set_pair_fusion(strait_ctx* c, int64_t min_pixels) {
     return STRAIT_OK;
 }
 
+strait_status strait_ctx_set_proj_fusion(strait_ctx* c, int64_t min_pixels) {
+    if (!c || min_pixels < 0) { set_error("ctx_set_proj_fusion: null context or negative size"); return STRAIT_E_INVALID; }
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->proj_min_pixels = min_pixels;
+    return STRAIT_OK;
+}
+
 strait_status strait_ctx_set_lp_yield(strait_ctx* c, int32_t layers_per_segment) {
     if (!c || layers_per_segment < 0) { set_error("ctx_set_lp_yield: null context or negative segment length"); return STRAIT_E_INVALID; }
     std::lock_guard<std::mutex> lk(c->mu);
@@ -657,6 +664,17 @@ strait_status strait_k_pointwise_pair(void* stream, const void* x, const void* w
     p.x = (const half_t*)x; p.w3 = (const half_t*)w3; p.b3 = b3; p.res = (const half_t*)res; p.y = (half_t*)y;
     p.w1 = (const half_t*)w1; p.b1 = b1; p.z = (half_t*)z;
     p.M = M; p.K1 = K1; p.N1 = N1; p.N2 = N2; p.act1 = act1; p.act2 = act2; p.hp = hp;
+    return launch_pointwise_pair(p, (hipStream_t)stream);
+}
+
+strait_status strait_k_pointwise_pair_proj(void* stream, const void* x, const void* x2, const void* w3, const float* b3, void* y,
+                                           const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t K2, int32_t N1,
+                                           int32_t N2, int32_t act1, int32_t act2, int32_t hp) {
+    if (!x2) { set_error("pointwise pair with projection: x2 is required"); return STRAIT_E_INVALID; }
+    PairParams p{};
+    p.x = (const half_t*)x; p.x2 = (const half_t*)x2; p.w3 = (const half_t*)w3; p.b3 = b3; p.y = (half_t*)y;
+    p.w1 = (const half_t*)w1; p.b1 = b1; p.z = (half_t*)z;
+    p.M = M; p.K1 = K1; p.K2 = K2; p.N1 = N1; p.N2 = N2; p.act1 = act1; p.act2 = act2; p.hp = hp;
     return launch_pointwise_pair(p, (hipStream_t)stream);
 }
 

@@ -50,12 +50,16 @@ int launch_conv(const ConvParams& p, hipStream_t stream);
 //   y[m, 0:N1] = act1(x[m, 0:K1] w3^T + b3 (+ res[m, 0:N1]));   z[m, 0:N2] = act2(y[m, 0:N1] w1^T + b1)
 // x [M][K1], w3 [N1][K1], res and y [M][N1], w1 [N2][N1], z [M][N2], all dense fp16; biases fp32 or nullptr.
 // z must not share memory with x or res (other workgroups may still be reading them).
+// With x2 (a second input [M][K2], for a block whose shortcut is a 1x1 projection of x2) the first product is
+// [x | x2] w3^T with w3 [N1][K1 + K2], and there is no res.
 struct PairParams {
     const half_t* x; const half_t* w3; const float* b3; const half_t* res; half_t* y;
     const half_t* w1; const float* b1; half_t* z;
     int M, K1, N1, N2, act1, act2, hp;
+    const half_t* x2; int K2;
 };
 bool pointwise_pair_supported(int K1, int N1, int N2);
+bool pointwise_pair_proj_supported(int K1, int K2, int N1, int N2);
 int launch_pointwise_pair(const PairParams& p, hipStream_t stream);
 
 int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, int Hp, int Wp, int Cpad,

@@ -146,6 +146,36 @@ struct Loader {
         op.info.weight_bytes = (int64_t)K * Kg * 2 + K * 4;
         return 0;
     }
+    // A block-closing 1x1 convolution and the 1x1 projection shortcut beside it as one weight matrix [K][C1 + C2] (each
+    // half folded and rounded exactly as conv_weights does it) and one bias (the two folded biases added in fp32).
+    int proj_pair_weights(const std::string& n3, unsigned C1, const std::string& nd, unsigned C2, unsigned K, Op& op) {
+        const unsigned ldw = C1 + C2;
+        std::vector<half_t> out((size_t)K * ldw, (half_t)0);
+        std::vector<float> bsum(K, 0.f);
+        unsigned off = 0;
+        for (int part = 0; part < 2; ++part) {
+            const std::string& name = part ? nd : n3;
+            const unsigned C = part ? C2 : C1;
+            const TensorView* w = c.find(name + ".w");
+            if (!w) return STRAIT_E_FORMAT;
+            if (!shape_is(w, {K, C, 1, 1})) { set_error("'%s.w': expected [%u,%u,1,1]", name.c_str(), K, C); return STRAIT_E_FORMAT; }
+            std::vector<float> scale, bias;
+            int rc = scale_bias(name, true, K, scale, bias);
+            if (rc) return rc;
+            for (unsigned k = 0; k < K; ++k) {
+                for (unsigned cc = 0; cc < C; ++cc) out[(size_t)k * ldw + off + cc] = (half_t)((float)w->data[k * C + cc] * scale[k]);
+                bsum[k] += bias[k];
+            }
+            off += C;
+        }
+        void *dw = nullptr, *db = nullptr;
+        int rc;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bsum.data(), bsum.size() * 4, &db))) return rc;
+        op.w_proj = (const half_t*)dw;
+        op.bias_proj = (const float*)db;
+        return 0;
+    }
     // Stem: OIHW [K][C][R][S] -> [K][R][Sv*Cpad] with taps s >= S and channels c >= C zero.
     int stem_weights(const std::string& name, bool bn, unsigned K, unsigned C, unsigned R, unsigned S, unsigned Sv, unsigned Cpad, Op& op) {
         const TensorView* w = c.find(name + ".w");
@@ -543,11 +573,13 @@ static int plan_resnet50(Model& m, Builder& b) {
             const int P2 = b.osz(P, 3, stride, 1), Q2 = b.osz(Q, 3, stride, 1);
             // The projection shortcut of a stage's first block depends only on the block input, as does
             // c1: it is issued first and runs on the side stream beside c1 and c2; c3 joins.
-            int sc = cur;
+            int sc = cur, down_idx = -1;
+            const int block_in = cur;
             if (bi == 0) {
                 sc = b.pl.get((size_t)P2 * Q2 * pln * 4);
                 if ((rc = b.conv(p + ".down", true, cur, P, Q, cin, pln * 4, 1, stride, 0, ACT_NONE, SLOT_NONE, sc, nullptr, nullptr))) return rc;
                 m.ops.back().side = 1;
+                down_idx = (int)m.ops.size() - 1;
             }
             const int t1 = carry_t1 >= 0 ? carry_t1 : b.pl.get((size_t)P * Q * pln);
             carry_t1 = -1;
@@ -555,7 +587,10 @@ static int plan_resnet50(Model& m, Builder& b) {
             const int t2 = b.pl.get((size_t)P2 * Q2 * pln);
             if ((rc = b.conv(p + ".c2", true, t1, P, Q, pln, pln, 3, stride, 1, ACT_RELU, SLOT_NONE, t2, nullptr, nullptr))) return rc;
             b.pl.put(t1);
-            if (bi == 0) b.pl.put(cur);
+            // a projection that may join the closing convolution's launch reads the block input there: keep it until then
+            const bool next_same = bi != nblocks[si] - 1;
+            const bool proj = bi == 0 && stride == 1 && next_same && pointwise_pair_proj_supported(pln, cin, pln * 4, pln);
+            if (bi == 0 && !proj) b.pl.put(cur);
             const int o = b.pl.get((size_t)P2 * Q2 * pln * 4);
             if ((rc = b.conv(p + ".c3", true, t2, P2, Q2, pln, pln * 4, 1, 1, 0, ACT_RELU, sc, o, nullptr, nullptr))) return rc;
             if (bi == 0) m.ops.back().join = 1;
@@ -567,7 +602,14 @@ static int plan_resnet50(Model& m, Builder& b) {
             if (!last && pointwise_pair_supported(pln, pln * 4, next_pln) && m.ops.back().ldw == pln) {
                 carry_t1 = b.pl.get((size_t)P2 * Q2 * next_pln);
                 m.ops.back().pair = bi == nblocks[si] - 1 ? 2 : 1;
+                if (proj) {
+                    Op& c3 = m.ops.back();
+                    if ((rc = b.ld.proj_pair_weights(p + ".c3", pln, p + ".down", cin, pln * 4, c3))) return rc;
+                    c3.proj_down = down_idx;
+                    m.ops[down_idx].proj_of = (int)m.ops.size() - 1;
+                }
             }
+            if (proj) b.pl.put(block_in);
             b.pl.put(t2);
             b.pl.put(sc);
             cur = o; cin = pln * 4; P = P2; Q = Q2;
@@ -866,10 +908,19 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     bool forked = false;
     hipStream_t main_stream = stream;
     int fused_away = -1;                                // op already computed by the pair launch of an earlier op
+    // whether op i (a block-closing pointwise convolution) runs as one launch with the op `pair` further on, and whether
+    // that launch also absorbs the block's projection shortcut; the projection op asks the same question about its block
+    auto pair_here = [&](int i) {
+        const Op& op = m.ops[i];
+        if (!op.pair || i + op.pair > last_layer || m.ctx->pair_min_pixels <= 0) return 0;
+        const long long pixels = (long long)batch * op.P * op.Q;
+        if (op.w_proj && pixels >= m.ctx->proj_min_pixels) return 2;
+        return pixels >= m.ctx->pair_min_pixels ? 1 : 0;
+    };
     for (int i = first_layer; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
         stream = main_stream;
-        if (i == fused_away) {
+        if (i == fused_away || (op.proj_of >= 0 && pair_here(op.proj_of) == 2)) {
             if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
             continue;
         }
@@ -892,11 +943,18 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
         int rc = 0;
         switch (op.kind) {
             case OP_CONV: {
-                if (op.pair && i + op.pair <= last_layer && m.ctx->pair_min_pixels > 0 && (long long)batch * op.P * op.Q >= m.ctx->pair_min_pixels) {
+                if (const int how = pair_here(i)) {
                     const Op& nx = m.ops[i + op.pair];
                     PairParams q{};
-                    q.x = (const half_t*)src; q.w3 = op.w; q.b3 = op.bias;
-                    q.res = (const half_t*)slot_ptr(m, in, op.res, 0, batch);
+                    q.x = (const half_t*)src;
+                    if (how == 2) {
+                        q.x2 = (const half_t*)slot_ptr(m, in, m.ops[op.proj_down].in, 0, batch);
+                        q.K2 = m.ops[op.proj_down].vC;
+                        q.w3 = op.w_proj; q.b3 = op.bias_proj;
+                    } else {
+                        q.w3 = op.w; q.b3 = op.bias;
+                        q.res = (const half_t*)slot_ptr(m, in, op.res, 0, batch);
+                    }
                     q.y = (half_t*)dst;
                     q.w1 = nx.w; q.b1 = nx.bias; q.z = (half_t*)slot_ptr(m, in, nx.out, nx.out_ref, batch);
                     q.M = batch * op.P * op.Q; q.K1 = op.vC; q.N1 = op.K; q.N2 = nx.K; q.act1 = op.act; q.act2 = nx.act; q.hp = hp;

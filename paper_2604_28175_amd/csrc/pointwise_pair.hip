@@ -43,14 +43,17 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int N1, int N2, int NW>
+template <int N1, int N2, int NW, bool DUAL>
 __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const PairParams p) {
-    constexpr int K1 = 64, KS1 = K1 / 16, CH = 64, NC = N1 / CH, NB2 = N2 / 32, LDC = CH + 8;
+    // DUAL: the block's shortcut is a 1x1 projection of a second 64-channel tensor.  Its product joins the first
+    // one's reduction (K1 = 64 + 64, the two weight matrices side by side) instead of arriving as a residual tensor.
+    constexpr int K1 = DUAL ? 128 : 64, KS1 = K1 / 16, CH = 64, NC = N1 / CH, NB2 = N2 / 32, LDC = CH + 8;
     constexpr int W3B = N1 * K1 * 2, W1B = N2 * N1 * 2, BIASB = (N1 + N2) * 4, PRIV = 32 * LDC * 2;
     static_assert(NC % 2 == 0 && N1 % 128 == 0 && (N2 == 64 || N2 == 128), "unsupported shape");
     static_assert(W3B + W1B + BIASB + NW * PRIV <= 160 * 1024, "LDS limit");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    half_t* W3s = (half_t*)smem;                       // [N1][64], chunk c of row r at c ^ ((r >> 1) & 7)
+    half_t* W3s = (half_t*)smem;                       // [N1][K1], chunk c of row r at c ^ swz3(r)
+    auto swz3 = [](int r) { return K1 == 64 ? (r >> 1) & 7 : r & 15; };
     half_t* W1s = (half_t*)(smem + W3B);               // [N2][N1], chunk c of row r at c ^ (r & 15)
     float* b3s = (float*)(smem + W3B + W1B);
     float* b1s = b3s + N1;
@@ -60,9 +63,9 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
     const int l32 = lane & 31, lh = lane >> 5;
     half_t* Cs = (half_t*)(smem + W3B + W1B + BIASB + wave * PRIV);   // this wavefront's own [32][LDC]
 
-    for (int id = tid; id < N1 * 8; id += 64 * NW) {
-        const int row = id >> 3, c = id & 7;
-        *(uint4*)(W3s + row * K1 + ((c ^ ((row >> 1) & 7)) * 8)) = *(const uint4*)(p.w3 + (long long)row * K1 + c * 8);
+    for (int id = tid; id < N1 * (K1 / 8); id += 64 * NW) {
+        const int row = id / (K1 / 8), c = id % (K1 / 8);
+        *(uint4*)(W3s + row * K1 + ((c ^ swz3(row)) * 8)) = *(const uint4*)(p.w3 + (long long)row * K1 + c * 8);
     }
     for (int id = tid; id < N2 * (N1 / 8); id += 64 * NW) {
         const int row = id / (N1 / 8), c = id % (N1 / 8);
@@ -91,13 +94,19 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
     auto clampm = [&](long long m) { return m < mlast ? m : mlast; };
     // operands requested ahead: input fragments of a tile, residual segments of a chunk
     auto load_x = [&](long long tile, half8 (&xf)[KS1]) {
-        const half_t* src = p.x + clampm(tile * 32 + l32) * K1 + lh * 8;
+        const long long off = clampm(tile * 32 + l32) * 64 + lh * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) xf[ks] = *(const half8*)(src + ks * 16);
+        for (int ks = 0; ks < 4; ++ks) xf[ks] = *(const half8*)(p.x + off + ks * 16);
+        if constexpr (DUAL) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) xf[4 + ks] = *(const half8*)(p.x2 + off + ks * 16);
+        }
     };
     auto load_res = [&](long long tile, int j, half8 (&rv)[4]) {
+        if constexpr (!DUAL) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rv[i] = *(const half8*)(p.res + clampm(tile * 32 + rrow + 8 * i) * N1 + j * CH + rc8 * 8);
+            for (int i = 0; i < 4; ++i) rv[i] = *(const half8*)(p.res + clampm(tile * 32 + rrow + 8 * i) * N1 + j * CH + rc8 * 8);
+        }
     };
     half8 xf[KS1], xn[KS1], rvA[4], rvB[4];
     const long long t0 = t < ntiles ? t : ntiles - 1;   // a wavefront with no tile still issues valid loads
@@ -130,7 +139,7 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
                     const int row = j * CH + a * 32 + l32;
-                    const half8 wf = *(const half8*)(W3s + row * K1 + (((ks * 2 + lh) ^ ((row >> 1) & 7)) * 8));
+                    const half8 wf = *(const half8*)(W3s + row * K1 + (((ks * 2 + lh) ^ swz3(row)) * 8));
                     acc1[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, xf[ks], acc1[a], 0, 0, 0);
                 }
 #pragma unroll
@@ -150,7 +159,8 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 half8 v = *(const half8*)(Cs + (rrow + 8 * i) * LDC + rc8 * 8);
-                v = __builtin_elementwise_min(__builtin_elementwise_max(v + rv[i], lo8), hi8);
+                if constexpr (!DUAL) v = v + rv[i];
+                v = __builtin_elementwise_min(__builtin_elementwise_max(v, lo8), hi8);
                 *(half8*)(Cs + (rrow + 8 * i) * LDC + rc8 * 8) = v;
                 vout[i] = v;
             }
@@ -207,10 +217,10 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
     }
 }
 
-template <int N1, int N2, int NW>
+template <int N1, int N2, int NW, bool DUAL>
 static int launch_pair_wave(const PairParams& p, hipStream_t stream) {
-    constexpr unsigned lds = N1 * 64 * 2 + N2 * N1 * 2 + (N1 + N2) * 4 + NW * 32 * 72 * 2;
-    auto kernel = pointwise_pair_wave_kernel<N1, N2, NW>;
+    constexpr unsigned lds = N1 * (DUAL ? 128 : 64) * 2 + N2 * N1 * 2 + (N1 + N2) * 4 + NW * 32 * 72 * 2;
+    auto kernel = pointwise_pair_wave_kernel<N1, N2, NW, DUAL>;
     static std::atomic<bool> configured{false};
     if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -226,19 +236,26 @@ static int launch_pair_wave(const PairParams& p, hipStream_t stream) {
 }
 
 bool pointwise_pair_supported(int K1, int N1, int N2) { return K1 == 64 && N1 == 256 && (N2 == 64 || N2 == 128); }
+bool pointwise_pair_proj_supported(int K1, int K2, int N1, int N2) { return K1 == 64 && K2 == 64 && N1 == 256 && N2 == 64; }
 
 int launch_pointwise_pair(const PairParams& p, hipStream_t stream) {
-    if (!p.x || !p.w3 || !p.res || !p.y || !p.w1 || !p.z || p.M <= 0) { set_error("pointwise pair: invalid parameters"); return -1; }
-    if (!pointwise_pair_supported(p.K1, p.N1, p.N2)) {
-        set_error("pointwise pair: unsupported shape (K1 %d, N1 %d, N2 %d)", p.K1, p.N1, p.N2);
+    const bool dual = p.x2 != nullptr;
+    if (!p.x || !p.w3 || (dual ? p.res != nullptr : !p.res) || !p.y || !p.w1 || !p.z || p.M <= 0) {
+        set_error("pointwise pair: invalid parameters (a residual tensor or a second input, not both, not neither)");
+        return -1;
+    }
+    if (dual ? !pointwise_pair_proj_supported(p.K1, p.K2, p.N1, p.N2) : !pointwise_pair_supported(p.K1, p.N1, p.N2)) {
+        set_error("pointwise pair: unsupported shape (K1 %d, K2 %d, N1 %d, N2 %d)", p.K1, dual ? p.K2 : 0, p.N1, p.N2);
         return -5;
     }
     if ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w3) | reinterpret_cast<uintptr_t>(p.y) |
-         reinterpret_cast<uintptr_t>(p.w1) | reinterpret_cast<uintptr_t>(p.z) | reinterpret_cast<uintptr_t>(p.res)) & 15) {
+         reinterpret_cast<uintptr_t>(p.w1) | reinterpret_cast<uintptr_t>(p.z) | reinterpret_cast<uintptr_t>(p.res) |
+         reinterpret_cast<uintptr_t>(p.x2)) & 15) {
         set_error("pointwise pair: pointers must be 16-byte aligned");
         return -1;
     }
-    const int rc = p.N2 == 64 ? launch_pair_wave<256, 64, 8>(p, stream) : launch_pair_wave<256, 128, 8>(p, stream);
+    const int rc = dual ? launch_pair_wave<256, 64, 8, true>(p, stream)
+                 : p.N2 == 64 ? launch_pair_wave<256, 64, 8, false>(p, stream) : launch_pair_wave<256, 128, 8, false>(p, stream);
     if (rc) return rc;
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("pointwise pair launch: %s", hipGetErrorString(e)); return -2; }

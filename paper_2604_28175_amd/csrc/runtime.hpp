@@ -45,6 +45,13 @@ struct Op {
     // A block-closing pointwise convolution whose output feeds the pointwise convolution `pair` ops further on (0 = none):
     // at large batches the two run as one launch (pointwise_pair.hip) and the second op is skipped.
     int pair = 0;
+    // Such a pair in a block whose shortcut is a 1x1 projection of the block input with the block's own stride 1: the
+    // projection can join the closing convolution's reduction (w_proj = [w | projection's w], bias_proj = the two biases
+    // added), and the projection's own launch is skipped.  proj_down: on the closing convolution, the index of the
+    // projection op; proj_of: on the projection op, the index of the closing convolution (-1 = none).
+    int proj_down = -1, proj_of = -1;
+    const half_t* w_proj = nullptr;
+    const float* bias_proj = nullptr;
     // implicit-GEMM addressing (elements), see ConvParams
     long long sN = 0; int sH = 0, sW = 0, stride_w = 1, pad_h = 0, pad_w = 0, vC = 0, vR = 0, vS = 0, vH = 0, vW = 0;
     int ldw = 0;
@@ -137,6 +144,7 @@ struct Context {
     bool stop = false;
     bool wave_priority = true;
     bool use_graphs = false;
+    long long proj_min_pixels = 3000;       // the same for pairs that absorb a projection shortcut: three launches become one
     long long pair_min_pixels = 300000;     // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
     int lp_yield_layers = 0;                // > 0: low-priority batches are issued in segments of this many layers and yield between them
     std::atomic<int> hp_in_flight{0};       // high-priority batches submitted and not yet complete

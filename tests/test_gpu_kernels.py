@@ -202,6 +202,55 @@ def test_pointwise_pair_rejects_other_shapes(S):
     assert e.value.status == S.E_INVALID
 
 
+@pytest.mark.parametrize("M", [9001, 70, 97001])
+def test_pointwise_pair_proj(S, M):
+    """The pair whose shortcut is a 1x1 projection of a second tensor: y = relu(x W3^T + x2 Wd^T + b3 + bd) with the two
+    products in one reduction, z = relu(fp16(y) W1^T + b1): against the oracle's operators, and bit for bit against one
+    product over the concatenated inputs."""
+    K1 = K2 = 64; N1, N2 = 256, 64
+    x, x2 = f16(R.standard_normal((M, K1))), f16(R.standard_normal((M, K2)))
+    w3 = f16(R.standard_normal((N1, K1)) * (0.5 / K1) ** 0.5)
+    wd = f16(R.standard_normal((N1, K2)) * (0.5 / K2) ** 0.5)
+    b3 = (R.standard_normal(N1) * 0.1).astype(np.float32)
+    bd = (R.standard_normal(N1) * 0.1).astype(np.float32)
+    w1 = f16(R.standard_normal((N2, N1)) * (2.0 / N1) ** 0.5)
+    b1 = (R.standard_normal(N2) * 0.1).astype(np.float32)
+    bsum = b3 + bd
+    y_ref = ops.relu(ops.linear(x, w3, None) + ops.linear(x2, wd, None) + bsum.astype(np.float64))
+    z_ref = ops.relu(ops.linear(y_ref.astype(np.float16), w1, b1))
+    wcat = np.ascontiguousarray(np.concatenate([w3, wd], axis=1))
+    dx, dx2, dw, db, dw1, db1 = dev(S, x), dev(S, x2), dev(S, wcat), dev(S, bsum), dev(S, w1), dev(S, b1)
+    y, z = S.k_pointwise_pair_proj(dx, dx2, dw, db, dw1, db1)
+    S.torch.cuda.synchronize()
+    check_kernel(y.float().cpu().numpy(), y_ref, f"pair-proj y {M}")
+    check_kernel(z.float().cpu().numpy(), z_ref, f"pair-proj z {M}", rel=2.0 ** -9)
+    if M * N1 > 128 * 4096:           # (below that the stand-alone kernel splits its reduction and adds in another order)
+        xcat = S.torch.cat([dx, dx2], dim=1).contiguous()
+        assert S.torch.equal(y, S.k_gemm(xcat, dw, db, S.ACT_RELU))
+
+
+def test_pointwise_pair_proj_integer_data_and_errors(S):
+    M, N1, N2 = 777, 256, 64
+    x = R.integers(-2, 3, (M, 64)).astype(np.float16)
+    x2 = R.integers(-2, 3, (M, 64)).astype(np.float16)
+    wcat = R.integers(-1, 2, (N1, 128)).astype(np.float16)
+    b = R.integers(-3, 4, N1).astype(np.float32)
+    w1 = (R.integers(-1, 2, (N2, N1)) * (R.random((N2, N1)) < 0.1)).astype(np.float16)     # sparse: sums stay exact in fp16
+    b1 = R.integers(-3, 4, N2).astype(np.float32)
+    y_ref = ops.relu(ops.linear(np.concatenate([x, x2], axis=1), wcat, b))
+    z_ref = ops.relu(ops.linear(y_ref, w1, b1))
+    assert np.abs(y_ref).max() < 2048 and np.abs(z_ref).max() < 2048
+    y, z = S.k_pointwise_pair_proj(dev(S, x), dev(S, x2), dev(S, wcat), dev(S, b), dev(S, w1), dev(S, b1))
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), y_ref)
+    assert np.array_equal(z.float().cpu().numpy().astype(np.float64), z_ref)
+    with pytest.raises(S.StraitError) as e:                      # the next stage's 128 channels do not fit beside the wider weights
+        S.k_pointwise_pair_proj(dev(S, x), dev(S, x2), dev(S, wcat), dev(S, b), S.torch.zeros((128, 256), dtype=S.torch.float16, device="cuda"), None)
+    assert e.value.status == S.E_SHAPE
+    with pytest.raises(S.StraitError) as e:
+        S.k_pointwise_pair_proj(dev(S, x), None, dev(S, wcat), dev(S, b), dev(S, w1), dev(S, b1))
+    assert e.value.status == S.E_INVALID
+
+
 @pytest.mark.parametrize("N,H,W,C,stride", [(2, 14, 14, 96, 1), (2, 15, 13, 144, 2), (1, 7, 7, 960, 1), (3, 28, 28, 32, 2), (1, 9, 10, 8, 1),
                                             # stride 1 with enough work for the column kernel: few channels, ragged height, many channels
                                             (6, 56, 56, 32, 1), (5, 30, 27, 144, 1), (16, 7, 7, 960, 1)])

@@ -91,6 +91,7 @@ def test_resnet50_fused_block_seams_equal_separate_launches(ctx):
     x = synth.default_image_batch(md, 6, 9)
     m = ctx.load(synth.pack(md), max_batch=6, n_instances=1)
     try:
+        ctx.set_proj_fusion(1 << 40)  # the first block's pair with its projection shortcut is not bit-identical: below
         ctx.set_pair_fusion(0)
         sep, _ = m.infer(x, prio=ctx.S.PRIO_HIGH)
         ctx.set_pair_fusion(1)
@@ -104,8 +105,18 @@ def test_resnet50_fused_block_seams_equal_separate_launches(ctx):
         for lname, key in (("s1b1.c1", "s1b1.c1"), ("s1b1.out", "s1b1.c3"), ("s1b2.out", "s1b2.c3"), ("s2b0.c1", "s2b0.c1")):
             got = m.read_activation(0, names.index(key), 6).astype(np.float64).reshape(ref.trace.acts[lname].shape)
             check_kernel(got, ref.trace.acts[lname], f"layer {lname}", rel=2.0 ** -8, abs_rel=1e-2)
+        # the first block's closing 1x1, its projection shortcut and the next block's opening 1x1 as one launch: one
+        # rounding fewer than the separate launches, so against the oracle only
+        ctx.set_proj_fusion(1)
+        proj, _ = m.infer(x, prio=ctx.S.PRIO_HIGH)
+        check_logits(proj["logits"], ref.logits, proj["top1"], "ResNet-50 b6, projection in the fused seam")
+        assert not np.array_equal(proj["logits"], fused["logits"])          # (the other path did run)
+        for lname, key in (("s1b0.out", "s1b0.c3"), ("s1b1.c1", "s1b1.c1"), ("s1b1.out", "s1b1.c3")):
+            got = m.read_activation(0, names.index(key), 6).astype(np.float64).reshape(ref.trace.acts[lname].shape)
+            check_kernel(got, ref.trace.acts[lname], f"layer {lname} (projection fused)", rel=2.0 ** -8, abs_rel=1e-2)
     finally:
         ctx.set_pair_fusion(300000)
+        ctx.set_proj_fusion(3000)
         m.free()
 
 
