@@ -139,9 +139,10 @@ strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
  * layers still fits the GPU's memory-side cache and two launches are as fast: batch 64 1.32 ms either way, batch 128
  * 2.29 -> 2.20 ms); 0 = always two launches.  Results are the same bit for bit. */
 strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
-/* The same threshold for a pair in the first block of a residual stage whose projection shortcut has stride 1 (ResNet-50's
- * first stage): there the one launch (strait_k_pointwise_pair_proj) also replaces the projection's launch, and neither the
- * projected tensor nor its read-back exists.  Default 3000 pixels (ResNet-50 from batch 1 on: batch 128 2.094 -> 2.014 ms,
+/* From how many output pixels on the closing 1x1 convolution of a residual stage's first block absorbs the block's 1x1
+ * projection shortcut as a second source of its reduction (strait_k_conv1x1_proj; in ResNet-50's first stage, where the
+ * projection has stride 1, as part of the fused pair, strait_k_pointwise_pair_proj): the projection's launch disappears,
+ * and neither the projected tensor nor its read-back exists.  Default 3000 pixels (ResNet-50 from batch 1 on: batch 128 2.094 -> 2.014 ms,
  * batch 16 0.610 -> 0.555 ms, batch 1 0.452 -> 0.449 ms).  Not bit-identical to separate launches: the sum of the two
  * products is rounded to fp16 once instead of the projection first.  With strait_ctx_set_pair_fusion(ctx, 0) no pair
  * is fused, this kind included. */
@@ -257,6 +258,15 @@ strait_status strait_k_gemm_noalloc(void* stream, const void* x, const void* w, 
 strait_status strait_k_pointwise_pair(void* stream, const void* x, const void* w3, const float* b3, const void* res, void* y,
                                       const void* w1, const float* b1, void* z, int32_t M, int32_t K1, int32_t N1, int32_t N2,
                                       int32_t act1, int32_t act2, int32_t hp);
+/* A block-closing 1x1 convolution that absorbs the block's 1x1 projection shortcut (Section 3.2 step (2): two members of
+ * the kernel sequence as one): the projection, which may subsample its input, is a second source of the reduction,
+ *     y[n,p,q,k] = act(bias[k] + sum_{c<C} x[n,p,q,c] w[k][c] + sum_{c<K2} x2[n, p*stride2, q*stride2, c] w[k][C + c])
+ * x [N][P][Q][C], x2 [N][H2][W2][K2] with (P-1)*stride2 < H2 and (Q-1)*stride2 < W2, w [Cout][C + K2], y [N][P][Q][Cout], dense
+ * fp16 device memory; bias fp32 [Cout] or NULL (the sum of the two layers' biases); act NONE, RELU or RELU6.  C and K2
+ * multiples of 64, Cout of 8 (E_SHAPE otherwise).  The sum is rounded to fp16 once. */
+strait_status strait_k_conv1x1_proj(void* stream, const void* x, int32_t N, int32_t P, int32_t Q, int32_t C, const void* x2,
+                                    int32_t H2, int32_t W2, int32_t K2, int32_t stride2, const void* w, const float* bias,
+                                    int32_t Cout, int32_t act, void* y, int32_t hp);
 /* The same pair where the first block's shortcut is a 1x1 projection of a second tensor (the first block of a residual
  * stage; Section 3.2 step (2)): the projection joins the first product's reduction instead of being written out and read
  * back as a residual,

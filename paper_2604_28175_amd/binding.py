@@ -91,6 +91,7 @@ _SIGS = {
     "strait_k_conv2d": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
+    "strait_k_conv1x1_proj": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_pointwise_pair": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_pointwise_pair_proj": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
@@ -388,6 +389,17 @@ def k_pointwise_pair(x, w3, b3, res, w1, b1, act1=ACT_RELU, act2=ACT_RELU, hp=0,
     _check(lib.strait_k_pointwise_pair(_stream(stream), _dev(x), _dev(w3), _dev(b3), _dev(res), _dev(y), _dev(w1), _dev(b1),
                                        _dev(z), m, k1, n1, n2, act1, act2, hp))
     return y, z
+
+
+def k_conv1x1_proj(x, x2, stride2, w, bias, act=ACT_NONE, hp=0, stream=None):
+    import torch
+    n, p_, q, c = x.shape
+    _, h2, w2, k2 = x2.shape
+    cout = w.shape[0]
+    y = torch.empty((n, p_, q, cout), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_conv1x1_proj(_stream(stream), _dev(x), n, p_, q, c, _dev(x2), h2, w2, k2, stride2, _dev(w), _dev(bias),
+                                     cout, act, _dev(y), hp))
+    return y
 
 
 def k_pointwise_pair_proj(x, x2, w3, b3, w1, b1, act1=ACT_RELU, act2=ACT_RELU, hp=0, stream=None):

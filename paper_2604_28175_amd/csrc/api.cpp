@@ -639,6 +639,31 @@ strait_status strait_k_conv2d(void* stream, const void* x, int32_t N, int32_t H,
     return rc;
 }
 
+strait_status strait_k_conv1x1_proj(void* stream, const void* x, int32_t N, int32_t P, int32_t Q, int32_t C, const void* x2,
+                                    int32_t H2, int32_t W2, int32_t K2, int32_t stride2, const void* w, const float* bias,
+                                    int32_t Cout, int32_t act, void* y, int32_t hp) {
+    if (N <= 0 || P <= 0 || Q <= 0 || C <= 0 || K2 <= 0 || Cout <= 0 || stride2 <= 0 || H2 <= 0 || W2 <= 0 ||
+        (long long)(P - 1) * stride2 >= H2 || (long long)(Q - 1) * stride2 >= W2 || (long long)N * P * Q > 0x7fffffffLL) {
+        set_error("conv1x1_proj: invalid shape (every output pixel needs its pixel of the second tensor)"); return STRAIT_E_SHAPE;
+    }
+    if (!x2) { set_error("conv1x1_proj: x2 is required"); return STRAIT_E_INVALID; }
+    ConvParams p{};
+    p.x = (const half_t*)x; p.w = (const half_t*)w; p.bias = bias; p.y = y;
+    p.M = N * P * Q; p.PQ = P * Q; p.Q = Q; p.H = P; p.W = Q; p.C = C; p.R = 1; p.S = 1;
+    p.stride_h = p.stride_w = 1; p.pad_h = p.pad_w = 0;
+    p.sN = (long long)P * Q * C; p.sH = Q * C; p.sW = C;
+    p.x2 = (const half_t*)x2; p.K2 = K2; p.stride2 = stride2; p.sN2 = (long long)H2 * W2 * K2; p.sH2 = W2 * K2; p.sW2 = K2;
+    p.Kg = C + K2; p.ldw = C + K2; p.Cout = Cout; p.ldy = Cout; p.act = act; p.hp = hp;
+    void* ws = nullptr;                                // small problems may take the split-K path, which needs an fp32 workspace
+    if ((long long)p.M * Cout <= 128LL * 4096) {
+        if (hipMalloc(&ws, SPLITK_WS_BYTES) != hipSuccess) { (void)hipGetLastError(); ws = nullptr; }
+        p.ws = (float*)ws; p.ws_bytes = ws ? SPLITK_WS_BYTES : 0;
+    }
+    const int rc = launch_conv(p, (hipStream_t)stream);
+    if (ws) { (void)hipStreamSynchronize((hipStream_t)stream); (void)hipFree(ws); }
+    return rc;
+}
+
 strait_status strait_k_gemm(void* stream, const void* x, const void* w, const float* bias, int32_t M, int32_t N,
                             int32_t K, int32_t act, const void* res, void* y, int32_t out_f32, int32_t hp) {
     if (M <= 0 || N <= 0 || K <= 0 || K % 8 != 0) { set_error("gemm: needs positive sizes and K %% 8 == 0"); return STRAIT_E_SHAPE; }

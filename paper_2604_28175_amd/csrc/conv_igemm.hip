@@ -332,8 +332,9 @@ constexpr int dma_tile_waves_per_simd() {
     return w < 1 ? 1 : (w > 8 ? 8 : w);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST>
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST, bool DUAL = false>
 __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, BN, BK, WGM, WGN, STAGES>())) conv_igemm_dma_kernel(const ConvParams p) {
+    static_assert(!DUAL || (MODE == MODE_1X1 && !HOIST && !GELU), "a second source belongs to a plain pointwise convolution");
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
     constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
@@ -411,6 +412,22 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
             }
         }
     }
+    // DUAL: the slices from p.C on come from the second tensor, addressed by output pixel with its own strides
+    const intx4 xrsrc2 = DUAL ? make_rsrc(p.x2, (unsigned)(p.x2_elems * 2)) : xrsrc;
+    unsigned xoff2[DUAL ? XI : 1];
+    if (DUAL) {
+#pragma unroll
+        for (int j = 0; j < XI; ++j) {
+            const int m = m0 + (j * NW + wave) * RPI + rsub;
+            xoff2[j] = OOB_OFFSET;
+            if (m < p.M) {
+                const int n = m / p.PQ, rem = m - n * p.PQ;
+                const int pp = rem / p.Q, qq = rem - pp * p.Q;
+                xoff2[j] = (unsigned)(((long long)n * p.sN2 + (long long)(pp * p.stride2) * p.sH2 +
+                                       (long long)(qq * p.stride2) * p.sW2 + cl * 8) * 2);
+            }
+        }
+    }
     unsigned woff[WI];
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
@@ -442,14 +459,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
         const unsigned sx = lds0 + (unsigned)(stage * STAGE) * 2u;
         const unsigned sw = sx + (unsigned)(BM * BK) * 2u;
         const bool live = ki < k_end;                  // slices past the end deposit zeros
-        const unsigned soff_x = MODE == MODE_1X1 ? (unsigned)ki * (BK * 2) : tap_off + (unsigned)cb * 2u;
+        const bool second = DUAL && ki * BK >= p.C;   // workgroup-uniform
+        const unsigned soff_x = MODE == MODE_1X1 ? (unsigned)(second ? ki * BK - p.C : ki * BK) * 2u : tap_off + (unsigned)cb * 2u;
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
             unsigned v = xoff[j];
+            if (DUAL && second) v = xoff2[j];
             if (MODE == MODE_GATHER8) v = ((tapmask[j] >> tap) & 1u) ? v : OOB_OFFSET;
             if (MODE == MODE_1X1 && ragged_k) v = (ki * BK + cl * 8 < p.Kg) ? v : OOB_OFFSET;
             if (!live) v = OOB_OFFSET;
-            dma16(xrsrc, v, live ? soff_x : 0u, sx + (unsigned)((j * NW + wave) * 1024));
+            dma16(second ? xrsrc2 : xrsrc, v, live ? soff_x : 0u, sx + (unsigned)((j * NW + wave) * 1024));
         }
 #pragma unroll
         for (int j = 0; j < WI; ++j)
@@ -951,6 +970,7 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
     };
     int rc;
     if (mode == MODE_1X1 && p.act == ACT_GELU) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, true, false>);
+    else if (mode == MODE_1X1 && p.x2) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, false, true>);
     else if (mode == MODE_1X1 && p.res && p.ksplit == 1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, true>);
     else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, false>);
     else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false, false>);
@@ -986,7 +1006,19 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         p.Q <= 0 || p.PQ <= 0 || p.stride_h <= 0 || p.stride_w <= 0) {
         set_error("conv: invalid parameters"); return -1;
     }
-    if (p.Kg != p.R * p.S * p.C) { set_error("conv: Kg != R*S*C"); return -5; }
+    if (p.x2) {
+        // a second source: both parts whole 64-wide slices, the first part a dense pointwise input, no residual
+        if (p.R != 1 || p.S != 1 || p.stride_h != 1 || p.stride_w != 1 || p.pad_h || p.pad_w || p.res || p.out_f32 || p.act == ACT_GELU ||
+            p.C % 64 != 0 || p.K2 <= 0 || p.K2 % 64 != 0 || p.Kg != p.C + p.K2 || p.sW != p.C || p.stride2 <= 0 ||
+            p.sW2 % 8 != 0 || p.sH2 % 8 != 0 || p.sN2 % 8 != 0 || p.Cout % 8 != 0 || p.ldy % 8 != 0 ||
+            (reinterpret_cast<uintptr_t>(p.x2) & 15)) {
+            set_error("conv: unsupported use of a second source"); return -5;
+        }
+        // the furthest element any output pixel reads from it
+        p.x2_elems = (long long)(p.M / p.PQ - 1) * p.sN2 + (long long)((p.PQ / p.Q - 1) * p.stride2) * p.sH2 +
+                     (long long)((p.Q - 1) * p.stride2) * p.sW2 + p.K2;
+        if (p.x2_elems * 2 > 0x7fffffffLL) { set_error("conv: second source too large"); return -5; }
+    } else if (p.Kg != p.R * p.S * p.C) { set_error("conv: Kg != R*S*C"); return -5; }
     if (p.ldw % 8 != 0 || p.ldw < p.Kg) { set_error("conv: weight pitch %d must be a multiple of 8 and >= %d", p.ldw, p.Kg); return -5; }
     if (p.ldy < p.Cout) { set_error("conv: ldy < Cout"); return -5; }
     if ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w) | reinterpret_cast<uintptr_t>(p.y) |
@@ -1051,6 +1083,8 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
             return launch_dma_tile<256, 128, 32, 2, 4, 3>(p, mode, stream);
         if (p.Kg >= 256 && p.Kg < 512 && p.Cout >= 1024 && tiles(128, 256) >= 192)   // wide outputs, medium reduction
             return launch_dma_tile<128, 256, 32, 2, 4, 2>(p, mode, stream);
+        if (p.Kg >= 256 && p.Kg < 512 && p.Cout >= 512 && tiles(256, 128) >= 512)    // the same with half the width (a block-closing
+            return launch_dma_tile<256, 128, 32, 2, 4, 3>(p, mode, stream);           // convolution with its projection: 81 -> 66 us at batch 128)
         if (p.Kg >= 512 && p.Cout >= 128 && t128 >= 192) {
             if (bk64) return t128 <= 256 ? launch_dma_tile<128, 128, 64, 2, 2, 3>(p, mode, stream)
                                          : launch_dma_tile<128, 128, 64, 2, 2, 2>(p, mode, stream);
@@ -1063,6 +1097,7 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         if (bk64) return launch_dma_tile<64, 64, 64, 2, 2, 3>(p, mode, stream);      // the same bytes in flight in half the steps
         return launch_dma_tile<64, 64, 32, 2, 2, 4>(p, mode, stream);
     }
+    if (p.x2) { set_error("conv: a second source needs the LDS-direct kernels (sizes out of their range)"); return -5; }
     if (p.Cout > 64 && tiles(128, 128) >= 512) return launch_tile<128, 128>(p, mode, staged, stream);
     if (tiles(128, 64) >= 512) return launch_tile<128, 64>(p, mode, staged, stream);
     return launch_tile<64, 64>(p, mode, staged, stream);

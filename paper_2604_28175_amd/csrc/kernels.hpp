@@ -42,6 +42,13 @@ struct ConvParams {
     int ksplit;              // filled in by launch_conv
     int tiles_n_shift;       // log2 of the number of tiles along Cout, or -1; filled in by the launcher
     int strip_w;             // 3x3 patch kernel: width of the strips a row is cut into; filled in by the launcher
+    // Optional second source of a 1x1 convolution with stride 1 (a block-closing convolution that absorbs the block's 1x1
+    // projection shortcut): reduction elements [C, C + K2) are x2[n*sN2 + p*stride2*sH2 + q*stride2*sW2 + (k - C)], and
+    // w is [Cout][C + K2].  Kg = C + K2; no res.
+    const half_t* x2;
+    int K2, stride2, sH2, sW2;
+    long long sN2;
+    long long x2_elems;      // extent of x2 in elements; filled in by launch_conv
 };
 
 int launch_conv(const ConvParams& p, hipStream_t stream);

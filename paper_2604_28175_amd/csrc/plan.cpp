@@ -590,7 +590,9 @@ static int plan_resnet50(Model& m, Builder& b) {
             // a projection that may join the closing convolution's launch reads the block input there: keep it until then
             const bool next_same = bi != nblocks[si] - 1;
             const bool proj = bi == 0 && stride == 1 && next_same && pointwise_pair_proj_supported(pln, cin, pln * 4, pln);
-            if (bi == 0 && !proj) b.pl.put(cur);
+            // elsewhere (stride 2) the closing convolution alone can absorb it, as a second source of its reduction
+            const bool proj_conv = bi == 0 && !proj && pln % 64 == 0 && cin % 64 == 0;
+            if (bi == 0 && !proj && !proj_conv) b.pl.put(cur);
             const int o = b.pl.get((size_t)P2 * Q2 * pln * 4);
             if ((rc = b.conv(p + ".c3", true, t2, P2, Q2, pln, pln * 4, 1, 1, 0, ACT_RELU, sc, o, nullptr, nullptr))) return rc;
             if (bi == 0) m.ops.back().join = 1;
@@ -609,7 +611,13 @@ static int plan_resnet50(Model& m, Builder& b) {
                     m.ops[down_idx].proj_of = (int)m.ops.size() - 1;
                 }
             }
-            if (proj) b.pl.put(block_in);
+            if (proj_conv) {
+                Op& c3 = m.ops.back();
+                if ((rc = b.ld.proj_pair_weights(p + ".c3", pln, p + ".down", cin, pln * 4, c3))) return rc;
+                c3.proj_down = down_idx;
+                m.ops[down_idx].proj_of = (int)m.ops.size() - 1;
+            }
+            if (proj || proj_conv) b.pl.put(block_in);
             b.pl.put(t2);
             b.pl.put(sc);
             cur = o; cin = pln * 4; P = P2; Q = Q2;
@@ -912,15 +920,19 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     // that launch also absorbs the block's projection shortcut; the projection op asks the same question about its block
     auto pair_here = [&](int i) {
         const Op& op = m.ops[i];
-        if (!op.pair || i + op.pair > last_layer || m.ctx->pair_min_pixels <= 0) return 0;
+        if (i > last_layer || m.ctx->pair_min_pixels <= 0) return 0;
         const long long pixels = (long long)batch * op.P * op.Q;
-        if (op.w_proj && pixels >= m.ctx->proj_min_pixels) return 2;
-        return pixels >= m.ctx->pair_min_pixels ? 1 : 0;
+        const bool with_proj = op.w_proj && pixels >= m.ctx->proj_min_pixels;
+        if (op.pair && i + op.pair <= last_layer) {
+            if (with_proj && pointwise_pair_proj_supported(op.vC, m.ops[op.proj_down].vC, op.K, m.ops[i + op.pair].K)) return 2;
+            if (pixels >= m.ctx->pair_min_pixels) return 1;
+        }
+        return with_proj ? 3 : 0;                       // 3: no pair, but the convolution takes the projection as a second source
     };
     for (int i = first_layer; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
         stream = main_stream;
-        if (i == fused_away || (op.proj_of >= 0 && pair_here(op.proj_of) == 2)) {
+        if (i == fused_away || (op.proj_of >= 0 && pair_here(op.proj_of) >= 2)) {
             if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
             continue;
         }
@@ -943,7 +955,8 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
         int rc = 0;
         switch (op.kind) {
             case OP_CONV: {
-                if (const int how = pair_here(i)) {
+                const int how = pair_here(i);
+                if (how == 1 || how == 2) {
                     const Op& nx = m.ops[i + op.pair];
                     PairParams q{};
                     q.x = (const half_t*)src;
@@ -972,6 +985,13 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 p.sN = op.sN; p.sH = op.sH; p.sW = op.sW;
                 p.Kg = op.vR * op.vS * op.vC; p.ldw = op.ldw;
                 p.Cout = op.K; p.ldy = op.K; p.act = op.act; p.out_f32 = op.out_f32; p.hp = hp;
+                if (how == 3) {
+                    const Op& dn = m.ops[op.proj_down];
+                    p.w = op.w_proj; p.bias = op.bias_proj; p.res = nullptr;
+                    p.x2 = (const half_t*)slot_ptr(m, in, dn.in, 0, batch);
+                    p.K2 = dn.vC; p.stride2 = dn.stride; p.sH2 = dn.sH; p.sW2 = dn.sW; p.sN2 = dn.sN;
+                    p.Kg = op.vC + dn.vC; p.ldw = p.Kg;
+                }
                 // the split-K workspace belongs to the main stream's launches; a branch running beside them goes without
                 if (stream == main_stream) { p.ws = in.splitk_ws; p.ws_bytes = SPLITK_WS_BYTES; }
                 rc = launch_conv(p, stream);

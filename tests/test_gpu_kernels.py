@@ -202,6 +202,45 @@ def test_pointwise_pair_rejects_other_shapes(S):
     assert e.value.status == S.E_INVALID
 
 
+@pytest.mark.parametrize("N,P,Q,C,H2,W2,K2,s2,Cout", [(2, 14, 14, 128, 28, 28, 256, 2, 512),      # few tiles: the reduction is split
+                                                        (16, 28, 28, 128, 56, 56, 256, 2, 512),    # 128-wide tiles
+                                                        (3, 7, 7, 512, 14, 14, 1024, 2, 2048),     # ragged rows, long second part
+                                                        (5, 8, 9, 64, 15, 17, 64, 2, 256),         # odd second tensor
+                                                        (4, 20, 20, 64, 20, 20, 64, 1, 256),       # stride 1
+                                                        (44, 28, 28, 128, 56, 56, 256, 2, 512)])   # enough tiles for the 256 x 128 shape
+def test_conv1x1_proj(S, N, P, Q, C, H2, W2, K2, s2, Cout):
+    """A pointwise convolution with a subsampling pointwise projection of a second tensor inside its reduction, against
+    the oracle's two convolutions added in fp64."""
+    x = f16(R.standard_normal((N, P, Q, C)))
+    x2 = f16(R.standard_normal((N, H2, W2, K2)))
+    w3 = f16(R.standard_normal((Cout, C)) * (0.5 / C) ** 0.5)
+    wd = f16(R.standard_normal((Cout, K2)) * (0.5 / K2) ** 0.5)
+    bias = (R.standard_normal(Cout) * 0.1).astype(np.float32)
+    sub = x2[:, ::s2, ::s2][:, :P, :Q]
+    ref = ops.relu(ops.linear(x, w3, None) + ops.linear(sub, wd, None) + bias.astype(np.float64))
+    wcat = np.ascontiguousarray(np.concatenate([w3, wd], axis=1))
+    y = S.k_conv1x1_proj(dev(S, x), dev(S, x2), s2, dev(S, wcat), dev(S, bias), S.ACT_RELU)
+    check_kernel(y.float().cpu().numpy(), ref, f"conv1x1+proj {N}x{P}x{Q}x{C}+{K2}->{Cout}")
+
+
+def test_conv1x1_proj_integer_data_and_errors(S):
+    N, P, Q, C, K2, Cout = 3, 9, 10, 64, 128, 72
+    x = R.integers(-2, 3, (N, P, Q, C)).astype(np.float16)
+    x2 = R.integers(-2, 3, (N, 2 * P, 2 * Q, K2)).astype(np.float16)
+    wcat = (R.integers(-1, 2, (Cout, C + K2)) * (R.random((Cout, C + K2)) < 0.5)).astype(np.float16)
+    bias = R.integers(-3, 4, Cout).astype(np.float32)
+    ref = ops.linear(np.concatenate([x, x2[:, ::2, ::2]], axis=-1), wcat, bias)
+    assert np.abs(ref).max() < 2048
+    y = S.k_conv1x1_proj(dev(S, x), dev(S, x2), 2, dev(S, wcat), dev(S, bias))
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref)
+    with pytest.raises(S.StraitError) as e:                      # a first part that is not whole 64-wide slices
+        S.k_conv1x1_proj(dev(S, x[..., :32].copy()), dev(S, x2), 2, dev(S, wcat[:, 32:].copy()), dev(S, bias))
+    assert e.value.status == S.E_SHAPE
+    with pytest.raises(S.StraitError) as e:                      # second tensor too small for the last output pixel
+        S.k_conv1x1_proj(dev(S, x), dev(S, x2[:, :2 * P - 2].copy()), 2, dev(S, wcat), dev(S, bias))
+    assert e.value.status == S.E_SHAPE
+
+
 @pytest.mark.parametrize("M", [9001, 70, 97001])
 def test_pointwise_pair_proj(S, M):
     """The pair whose shortcut is a 1x1 projection of a second tensor: y = relu(x W3^T + x2 Wd^T + b3 + bd) with the two
