@@ -24,6 +24,9 @@
 //   - the residual of the chunk after next and the input fragments of the next tile are requested ahead, across tile
 //     boundaries, and always before the stores of the current chunk (returns are counted in issue order: a load issued
 //     behind a store is not seen to arrive before that store is acknowledged);
+//     with 128 output channels the accumulators leave no registers for a second set of input fragments, and the next
+//     tile's are requested at the end of the current tile instead of at its start (with the early request the compiler
+//     spilled 23 registers per lane: 155 -> 124 us at batch 128);
 //   - rounding points are those of the two separate launches (fp32 accumulate, + bias, one rounding to fp16, residual
 //     add and clamp in fp16), and the second product reduces over the channels in ascending order in 16-wide MFMA
 //     steps like the stand-alone kernel, so the results are the same bit for bit.
@@ -108,7 +111,8 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
             for (int i = 0; i < 4; ++i) rv[i] = *(const half8*)(p.res + clampm(tile * 32 + rrow + 8 * i) * N1 + j * CH + rc8 * 8);
         }
     };
-    half8 xf[KS1], xn[KS1], rvA[4], rvB[4];
+    constexpr bool XPRE = N2 <= 64;                     // with 128 outputs the next tile's fragments do not fit in registers beside the accumulators
+    half8 xf[KS1], xn[XPRE ? KS1 : 1], rvA[4], rvB[4];
     const long long t0 = t < ntiles ? t : ntiles - 1;   // a wavefront with no tile still issues valid loads
     load_x(t0, xf);
     load_res(t0, 0, rvA);
@@ -124,7 +128,7 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
         for (int a = 0; a < NB2; ++a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc2[a][v] = 0.f;
-        load_x(tn, xn);
+        if constexpr (XPRE) load_x(tn, xn);
         __builtin_amdgcn_sched_barrier(0);
 
         auto chunk = [&](int j, half8 (&rv)[4]) {
@@ -213,7 +217,8 @@ __global__ void __launch_bounds__(64 * NW, 1) pointwise_pair_wave_kernel(const P
             wave_sync();
         }
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) xf[ks] = xn[ks];
+        for (int ks = 0; ks < KS1; ++ks) { if constexpr (XPRE) xf[ks] = xn[ks]; }
+        if constexpr (!XPRE) { if (t + stride < ntiles) load_x(t + stride, xf); }
     }
 }
 
