@@ -332,9 +332,15 @@ constexpr int dma_tile_waves_per_simd() {
     return w < 1 ? 1 : (w > 8 ? 8 : w);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST, bool DUAL = false>
-__global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, BN, BK, WGM, WGN, STAGES>())) conv_igemm_dma_kernel(const ConvParams p) {
+// KG > 1: the workgroup holds KG groups of WGM x WGN wavefronts, all on the same output tile; group g reduces the g-th
+// part of the slices in a ring of its own, the groups step through their parts together (the barriers are the
+// workgroup's), and at the end groups 1.. hand their partial sums to group 0 through LDS, which adds them in group
+// order and finishes the tile.  A split reduction without a second launch, for the small batches where one more
+// launch costs as much as the convolution.
+template <int BM, int BN, int BK, int WGM, int WGN, int MODE, int STAGES, bool GELU, bool HOIST, bool DUAL = false, int KG = 1>
+__global__ void __launch_bounds__(64 * WGM * WGN * KG, (KG > 1 ? WGM * WGN * KG / 4 : dma_tile_waves_per_simd<BM, BN, BK, WGM, WGN, STAGES>())) conv_igemm_dma_kernel(const ConvParams p) {
     static_assert(!DUAL || (MODE == MODE_1X1 && !HOIST && !GELU), "a second source belongs to a plain pointwise convolution");
+    static_assert(KG == 1 || (!GELU && !DUAL && KG * STAGES * (BM + BN) * BK * 2 + 1024 <= 160 * 1024 && WGM * WGN * KG <= 16), "groups: LDS or workgroup limit");
     constexpr int CPRW = BK / 8;                       // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPRW;                     // rows covered by one wave-wide transfer
     constexpr int SWD = 16 / CPRW;                     // rows that share a bank window
@@ -348,12 +354,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
     static_assert(MODE == MODE_1X1 || MODE == MODE_GATHER8, "vector modes only");
     static_assert(STAGES >= 2 && STAGES * STAGE * 2 <= 160 * 1024 && BM * LDC * 2 <= 160 * 1024, "LDS limit");
 
-    extern __shared__ __attribute__((aligned(1024))) half_t smem[];    // max(STAGES * STAGE, BM * LDC) halfs
+    extern __shared__ __attribute__((aligned(1024))) half_t smem_all[];    // max(KG * STAGES * STAGE, BM * LDC) halfs
+    const int group = KG > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x / NT) : 0;
+    half_t* const smem = smem_all + group * (STAGES * STAGE);          // this group's ring
     const unsigned lds0 = (unsigned)(uintptr_t)smem;
 
     if (p.hp) __builtin_amdgcn_s_setprio(3);
 
-    const int tid = threadIdx.x;
+    const int tid = (int)threadIdx.x - group * NT;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave % WGM) * TM, wn0 = (wave / WGM) * TN;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -367,7 +375,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
     }
     // split-K: the grid holds ksplit copies of the tile grid; copy z reduces slices [k_begin, k_end)
     int zsplit = 0, tile = logical;
-    if (p.ksplit > 1) {
+    if (KG > 1) zsplit = group;
+    else if (p.ksplit > 1) {
         const int ntiles = gridDim.x / p.ksplit;
         zsplit = logical / ntiles;
         tile = logical - zsplit * ntiles;
@@ -437,10 +446,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
 
     // ---- workgroup-uniform position of the slice being issued ---------------------------------
     const int nk_all = (p.Kg + BK - 1) / BK;
-    const int kchunk = (nk_all + p.ksplit - 1) / p.ksplit;
+    const int kparts = KG > 1 ? KG : p.ksplit;
+    const int kchunk = (nk_all + kparts - 1) / kparts;
     const int k_begin = zsplit * kchunk;
     const int k_end = k_begin + kchunk < nk_all ? k_begin + kchunk : nk_all;
-    const int nk = k_end > k_begin ? k_end - k_begin : 0;
+    // (the groups of one workgroup share its barriers: all of them take kchunk steps, slices past a group's part arrive as zeros)
+    const int nk = KG > 1 ? kchunk : (k_end > k_begin ? k_end - k_begin : 0);
     const bool ragged_k = (p.Kg & (BK - 1)) != 0;      // only possible for 1x1 / GEMM
     int ki = k_begin;                                  // slice index
     int tap = 0, ts = 0, cb = 0;                       // filter tap, its column, channel base
@@ -495,12 +506,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
 
     // The tile's bias row goes to LDS with the very first transfer (channels past Cout, or no bias at all,
     // arrive as zeros), so that the epilogue does not start with a round trip to L2.
-    constexpr unsigned BIAS_LDS = (STAGES * STAGE > BM * LDC ? STAGES * STAGE : BM * LDC) * 2;   // byte offset
+    constexpr unsigned BIAS_LDS = (KG * STAGES * STAGE > BM * LDC ? KG * STAGES * STAGE : BM * LDC) * 2;   // byte offset
     static_assert(BN <= 256, "bias row: one transfer carries 256 floats");
-    if (wave == 0) {
+    if (wave == 0) {                                   // (every group fetches it, so that the wavefronts' transfer counts agree)
         const intx4 brsrc = make_rsrc(p.bias, p.bias ? (unsigned)p.Cout * 4u : 0u);
         const int c = n0 + lane * 4;
-        dma16(brsrc, (p.bias && lane * 4 < BN && c + 3 < p.Cout) ? (unsigned)c * 4u : OOB_OFFSET, 0u, lds0 + BIAS_LDS);
+        dma16(brsrc, (p.bias && lane * 4 < BN && c + 3 < p.Cout) ? (unsigned)c * 4u : OOB_OFFSET, 0u, (unsigned)(uintptr_t)smem_all + BIAS_LDS);
     }
 
 #pragma unroll
@@ -543,6 +554,34 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
     }
     wait_loads_then_barrier<0>();                      // trailing transfers have landed; LDS is free
 
+    // ---- groups: partial sums of groups 1.. to group 0 through LDS, added in group order ----------------------
+    if (KG > 1) {
+        float* xch = (float*)smem_all;                 // [KG - 1][NW][TNB * TMB * 16][64 lanes]
+        if (group > 0) {
+            float* dst = xch + ((group - 1) * NW + wave) * (TNB * TMB * 16 * 64) + lane;
+#pragma unroll
+            for (int a = 0; a < TNB; ++a)
+#pragma unroll
+                for (int b = 0; b < TMB; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((a * TMB + b) * 16 + v) * 64] = acc[a][b][v];
+        }
+        __syncthreads();
+        if (group == 0) {
+            for (int g = 1; g < KG; ++g) {
+                const float* src = xch + ((g - 1) * NW + wave) * (TNB * TMB * 16 * 64) + lane;
+#pragma unroll
+                for (int a = 0; a < TNB; ++a)
+#pragma unroll
+                    for (int b = 0; b < TMB; ++b)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[a][b][v] += src[((a * TMB + b) * 16 + v) * 64];
+            }
+        }
+        __syncthreads();                               // before the epilogue parks the output tile in the same memory
+    }
+    const bool finisher = KG == 1 || group == 0;       // the other groups only keep the epilogue's barrier company
+
     // ---- split-K: fp32 partial sums to this copy's slab; a second kernel reduces and finishes ------
     if (p.ksplit > 1) {
         float* slab = p.ws + (long long)zsplit * p.M * p.Cout;
@@ -573,7 +612,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
     // (HOIST) request it right after the reduction, before the staging barrier: that takes its latency
     // off the path between the last MFMA and the stores.
     constexpr int CPR = BN / 8, NCH = BM * CPR / NT;
-    half_t* Cs = smem;
+    half_t* Cs = smem_all;
     const bool fuse_act = (p.res == nullptr);
     const half_t lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? (half_t)0.f : (half_t)-INFINITY;
     const half_t hi = p.act == ACT_RELU6 ? (half_t)6.f : (half_t)INFINITY;
@@ -590,16 +629,17 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
         if (m < p.M && n < p.Cout) r = *(const half8*)(p.res + (long long)m * p.ldy + n);
         return r;
     };
-    const float* bias_s = (const float*)((const char*)smem + BIAS_LDS);
+    const float* bias_s = (const float*)((const char*)smem_all + BIAS_LDS);
     auto bias4 = [&](int a, int g, float (&bv)[4]) {
         const float4 b4 = *(const float4*)(bias_s + wn0 + a * 32 + 8 * g + 4 * lh);
         bv[0] = b4.x; bv[1] = b4.y; bv[2] = b4.z; bv[3] = b4.w;
     };
     half8 rv[HOIST ? NCH : 1];
-    if (HOIST && !fuse_act) {
+    if (HOIST && !fuse_act && finisher) {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) rv[i] = residual_chunk(i);
     }
+    if (finisher)
 #pragma unroll
     for (int a = 0; a < TNB; ++a)
 #pragma unroll
@@ -621,6 +661,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, (dma_tile_waves_per_simd<BM, B
             }
         }
     __syncthreads();
+    if (!finisher) return;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
         const int id = tid + i * NT;
@@ -985,6 +1026,42 @@ static int launch_dma_tile(const ConvParams& p, int mode, hipStream_t stream) {
 }
 
 
+// The same tile with the reduction split over KG groups of wavefronts inside the workgroup (no second launch).
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, int KG>
+static int launch_dma_tile_groups(const ConvParams& p, int mode, hipStream_t stream) {
+    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN);
+    if (tiles <= 0 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
+    constexpr unsigned ring = KG * STAGES * (BM + BN) * BK * 2, ctile = BM * (BN + 8) * 2;
+    constexpr unsigned lds = (ring > ctile ? ring : ctile) + 1024;
+    static_assert(lds <= 160 * 1024, "LDS limit");
+    dim3 grid((unsigned)tiles), block(64 * WGM * WGN * KG);
+    ConvParams q = p;
+    q.ksplit = 1;
+    {
+        const int tn = (p.Cout + BN - 1) / BN;
+        q.tiles_n_shift = -1;
+        for (int sft = 0; sft < 31; ++sft) if ((1 << sft) == tn) q.tiles_n_shift = sft;
+    }
+    auto go = [&](auto kernel) -> int {
+        static std::atomic<bool> configured{false};
+        if (!configured.load(std::memory_order_acquire)) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
+        }
+        configured.store(true, std::memory_order_release);
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, q);
+        return 0;
+    };
+    int rc;
+    if (mode == MODE_1X1 && p.res) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, true, false, KG>);
+    else if (mode == MODE_1X1) rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_1X1, STAGES, false, false, false, KG>);
+    else rc = go(conv_igemm_dma_kernel<BM, BN, BK, WGM, WGN, MODE_GATHER8, STAGES, false, false, false, KG>);
+    if (rc) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
+    return 0;
+}
+
 template <int BM, int BN>
 static int launch_tile(const ConvParams& p, int mode, bool staged, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.Cout + BN - 1) / BN);
@@ -1039,21 +1116,30 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
     // (GELU after a residual add is left to the first kernel: this one applies GELU before the staging)
     const bool regular = (mode == MODE_1X1 && !(p.act == ACT_GELU && p.res)) || (mode == MODE_GATHER8 && p.C % 32 == 0 && p.R * p.S <= 32 && p.act != ACT_GELU);
     // Few output tiles and a long reduction (small batches, late layers): one workgroup per tile
-    // would leave most CUs idle behind a serial chain of slices.  Split the reduction over
-    // ksplit workgroups per tile, each writing an fp32 slab, and reduce in a second launch.
-    const bool split_ok = regular && small && p.ws && p.Cout % 8 == 0 && p.ldy % 8 == 0 &&
-                          (reinterpret_cast<uintptr_t>(p.ws) & 15) == 0;
-    if (split_ok) {
+    // would leave most CUs idle behind a serial chain of slices.  Split the reduction: over two groups of
+    // wavefronts inside the workgroup where a shallow split will do, else over ksplit workgroups per tile,
+    // each writing an fp32 slab, with a second launch that reduces them.
+    if (regular && small && p.Cout % 8 == 0 && p.ldy % 8 == 0) {
         const long long t = tiles(64, 64);
         const int nk = (p.Kg + 31) / 32;
-        if (t <= 128 && nk >= 8) {
-            // about one workgroup per CU and a bit hides the chain of slices; a layer that streams megabytes of
-            // weights for a handful of rows (the fully connected layers of a plain CNN) is bound by the bytes in
-            // flight and takes four times as many
-            const long long target = (long long)p.Cout * p.Kg * 2 >= (8LL << 20) ? 1280 : 320;
-            long long ks = (target + t - 1) / t;
-            if (ks > nk / 4) ks = nk / 4;
-            if (ks > 32) ks = 32;
+        // about one workgroup per CU and a bit hides the chain of slices; a layer that streams megabytes of
+        // weights for a handful of rows (the fully connected layers of a plain CNN) is bound by the bytes in
+        // flight and takes four times as many
+        const long long target = (long long)p.Cout * p.Kg * 2 >= (8LL << 20) ? 1280 : 320;
+        long long ks = (target + t - 1) / t;
+        if (ks > nk / 4) ks = nk / 4;
+        if (ks > 32) ks = 32;
+        // Up to an eight-way split, and up to one tile per CU: two groups of wavefronts in one workgroup, half of the
+        // slices each and no second launch (ResNet-50 batch 8: 1024 -> 256 at 14 x 14 10.7 -> 6.3 us, its 3x3 14.1 -> 12.0 us;
+        // batch 16, 196 tiles, the same 3x3 13.7 -> 11.9 us; four groups with shallower rings are no faster, and from 400
+        // tiles on the groups cost more than they save).  Deeper splits are layers that stream megabytes of weights
+        // for a few rows and need the workgroups (512-channel 3x3 at 7 x 7, batch 1: 12.8 us split 32 ways, 18.7 us in
+        // two groups).
+        if (t <= 256 && nk >= 8 && ks <= 8 && (ks > 1 || t > 128) && staged && !p.x2 && p.act != ACT_GELU) {
+            if (mode == MODE_1X1 && p.Kg % 64 == 0) return launch_dma_tile_groups<64, 64, 64, 2, 2, 3, 2>(p, mode, stream);
+            return launch_dma_tile_groups<64, 64, 32, 2, 2, 4, 2>(p, mode, stream);
+        }
+        if (t <= 128 && nk >= 8 && p.ws && (reinterpret_cast<uintptr_t>(p.ws) & 15) == 0) {
             while (ks > 1 && ks * (long long)p.M * p.Cout * 4 > (long long)p.ws_bytes) --ks;
             if (ks > 1) {
                 p.ksplit = (int)ks;

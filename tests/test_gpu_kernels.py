@@ -59,6 +59,12 @@ CONV_CASES = [
     (16, 112, 112, 64, 128, 3, 1, 1, 1, False, False),  # rows cut into two strips of 56; two input slices
     (48, 64, 64, 32, 128, 3, 1, 1, 0, False, False),    # 64-pixel rows: four patch transfers per wave
     (12, 128, 128, 32, 128, 3, 1, 1, 2, False, False),  # two strips of 64: four transfers per wave with real pixels on the strips' sides
+    # few tiles and a reduction worth splitting two to eight ways: two groups of wavefronts in one workgroup, half the slices each
+    (8, 14, 14, 1024, 256, 1, 1, 0, 1, False, False),   # pointwise, 64-wide slices, 16 of them
+    (2, 14, 14, 512, 256, 1, 1, 0, 1, True, False),     # pointwise with residual
+    (8, 14, 14, 256, 256, 3, 1, 1, 1, False, False),    # 3x3: 72 slices of 32
+    (1, 10, 10, 264, 64, 1, 1, 0, 0, False, False),     # nine 32-wide slices, the last one ragged: the second group's fifth slice is empty
+    (3, 9, 9, 160, 96, 3, 2, 1, 2, False, False),       # stride 2, ragged tiles in both directions, 45 slices
 ]
 
 
@@ -77,6 +83,19 @@ def test_conv2d(S, case):
     y = S.k_conv2d(dev(S, x), dev(S, w_krsc), dev(S, b), stride, pad, act, None if res is None else dev(S, res), out_f32)
     S.torch.cuda.synchronize()
     check_kernel(y.float().cpu().numpy(), ref, f"conv {case}")
+
+
+def test_conv2d_split_in_the_workgroup_integer_data_is_bit_exact(S):
+    """The reduction split over two groups of wavefronts of one workgroup (few tiles, 9 to 32 slices), pointwise and 3x3:
+    exact on integer data, partial sums and their hand-over included."""
+    for (N, H, W, C, K, Rk, stride, pad) in ((4, 14, 14, 512, 128, 1, 1, 0), (1, 10, 10, 264, 64, 1, 1, 0), (2, 14, 14, 96, 64, 3, 1, 1)):
+        x = R.integers(-2, 3, (N, H, W, C)).astype(np.float16)
+        w = (R.integers(-1, 2, (K, C, Rk, Rk)) * (R.random((K, C, Rk, Rk)) < 0.2)).astype(np.float16)
+        b = R.integers(-5, 6, K).astype(np.float32)
+        ref = ops.conv2d(x, w, b, stride, pad)
+        assert np.abs(ref).max() < 2048
+        y = S.k_conv2d(dev(S, x), dev(S, np.ascontiguousarray(np.transpose(w, (0, 2, 3, 1)))), dev(S, b), stride, pad)
+        assert np.array_equal(y.float().cpu().numpy().astype(np.float64), ref), (N, H, W, C, K, Rk)
 
 
 def test_conv2d_integer_data_is_bit_exact(S):
@@ -163,7 +182,7 @@ def test_pointwise_pair(S, M, K1, N1, N2, use_res):
     check_kernel(z.float().cpu().numpy(), z_ref, f"pair z {M}x{N1}x{N2}", rel=2.0 ** -9)
     y2 = S.k_gemm(dx, dw3, db3, S.ACT_RELU, dres)
     assert S.torch.equal(y, y2)
-    if M * N2 > 128 * 4096:           # (below that the stand-alone kernel splits its reduction and adds in another order)
+    if -(-M // 64) * -(-N2 // 64) > 256:   # (with fewer tiles the stand-alone kernel splits its reduction and adds in another order)
         assert S.torch.equal(z, S.k_gemm(y2, dw1, db1, S.ACT_RELU))
 
 
