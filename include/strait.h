@@ -143,8 +143,8 @@ strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
 /* From how many output pixels on the closing 1x1 convolution of a residual stage's first block absorbs the block's 1x1
  * projection shortcut as a second source of its reduction (strait_k_conv1x1_proj; in ResNet-50's first stage, where the
  * projection has stride 1, as part of the fused pair, strait_k_pointwise_pair_proj): the projection's launch disappears,
- * and neither the projected tensor nor its read-back exists.  Default 3000 pixels (ResNet-50 from batch 1 on: batch 128
- * 2.21 -> 2.06 ms, batch 16 0.610 -> 0.531 ms, batch 1 0.452 -> 0.436 ms).  Not bit-identical to separate launches: the sum of the two
+ * and neither the projected tensor nor its read-back exists.  Default 1, i.e. always (ResNet-50: batch 128 2.21 -> 2.06 ms,
+ * batch 16 0.610 -> 0.531 ms, batch 8 0.491 -> 0.468 ms, batch 1 0.452 -> 0.436 ms).  Not bit-identical to separate launches: the sum of the two
  * products is rounded to fp16 once instead of the projection first.  With strait_ctx_set_pair_fusion(ctx, 0) no pair
  * is fused, this kind included. */
 strait_status strait_ctx_set_proj_fusion(strait_ctx* ctx, int64_t min_pixels);

@@ -144,7 +144,7 @@ struct Context {
     bool stop = false;
     bool wave_priority = true;
     bool use_graphs = false;
-    long long proj_min_pixels = 3000;       // the same for pairs that absorb a projection shortcut: three launches become one
+    long long proj_min_pixels = 1;          // the same for pairs that absorb a projection shortcut: three launches become one
     long long pair_min_pixels = 40000;      // from this many output pixels on, marked pairs of pointwise convolutions run as one launch (0 = never)
     int lp_yield_layers = 0;                // > 0: low-priority batches are issued in segments of this many layers and yield between them
     std::atomic<int> hp_in_flight{0};       // high-priority batches submitted and not yet complete

@@ -116,7 +116,7 @@ def test_resnet50_fused_block_seams_equal_separate_launches(ctx):
             check_kernel(got, ref.trace.acts[lname], f"layer {lname} (projection fused)", rel=2.0 ** -8, abs_rel=1e-2)
     finally:
         ctx.set_pair_fusion(40000)
-        ctx.set_proj_fusion(3000)
+        ctx.set_proj_fusion(1)
         m.free()
 
 
