@@ -1134,8 +1134,9 @@ int launch_conv(const ConvParams& params, hipStream_t stream) {
         // batch 16, 196 tiles, the same 3x3 13.7 -> 11.9 us; four groups with shallower rings are no faster, and from 400
         // tiles on the groups cost more than they save).  Deeper splits are layers that stream megabytes of weights
         // for a few rows and need the workgroups (512-channel 3x3 at 7 x 7, batch 1: 12.8 us split 32 ways, 18.7 us in
-        // two groups).
-        if (t <= 256 && nk >= 8 && ks <= 8 && (ks > 1 || t > 128) && staged && !p.x2 && p.act != ACT_GELU) {
+        // two groups; the same layer at batch 8, split six ways: 14.3 against 19.5 us, so reductions of more than 96
+        // slices keep the slabs wherever those are an option).
+        if (t <= 256 && nk >= 8 && ks <= 8 && (t > 128 || (ks > 1 && nk <= 96)) && staged && !p.x2 && p.act != ACT_GELU) {
             if (mode == MODE_1X1 && p.Kg % 64 == 0) return launch_dma_tile_groups<64, 64, 64, 2, 2, 3, 2>(p, mode, stream);
             return launch_dma_tile_groups<64, 64, 32, 2, 2, 4, 2>(p, mode, stream);
         }
