@@ -31,6 +31,14 @@
 //     add and clamp in fp16), and the second product reduces over the channels in ascending order in 16-wide MFMA
 //     steps like the stand-alone kernel, so the results are the same bit for bit.
 //
+// DUAL: in the first block of the stage the shortcut is not a tensor but a 1x1 projection of the block input x2
+// [M][64].  A projection added to a pointwise convolution is one product over the two inputs side by side,
+//     y = act1([x | x2] [W3 | Wd]^T + (b3 + bd)),
+// so this instantiation reduces over 128 channels (the loader stores the two weight matrices side by side, 64 KB in
+// LDS, and one summed bias), takes its second half of input fragments from x2, and reads no residual: the projection's
+// own launch and the tensor it would write and this kernel read back do not exist.  The sum is rounded to fp16 once
+// (separate launches round the projection first).
+//
 // (A version with one 128-pixel tile per workgroup, the y chunk shared by four wavefronts and weight fragments fetched
 // from L2 per wavefront was measured first: three barriers per chunk and the weight traffic held it to 121-132 us on
 // the first stage's shape, against 111 us for this one and 158 us for the two separate launches; with 128 input
