@@ -137,7 +137,8 @@ strait_status strait_ctx_set_graphs(strait_ctx* ctx, int32_t enabled);
  * block's opening 1x1 convolution, which reads nothing but the first one's output, run as one launch
  * (strait_k_pointwise_pair).  Default 40000 (ResNet-50 at batch 16 and above: batch 128 2.29 -> 2.20 ms, batch 64 1.233 ->
  * 1.210 ms, batch 16 0.552 -> 0.543 ms; at batch 8 and below the two launches, which may split their reductions, are 1 %
- * faster); 0 = always two launches.  Results are the same bit for bit.  A graph that strait_ctx_set_graphs has
+ * faster); 0 = always two launches, and every other fusion of launches off as well (projection shortcuts, the first
+ * block's opening convolution inside the stem launch): the layer-by-layer plan.  Results are the same bit for bit.  A graph that strait_ctx_set_graphs has
  * already captured keeps the launches it was captured with: set this before the first batch. */
 strait_status strait_ctx_set_pair_fusion(strait_ctx* ctx, int64_t min_pixels);
 /* From how many output pixels on the closing 1x1 convolution of a residual stage's first block absorbs the block's 1x1

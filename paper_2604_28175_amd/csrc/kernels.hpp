@@ -74,8 +74,9 @@ int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, in
 // 7x7 stride-2 pad-3 convolution of a 3-channel image to 64 channels + bias + ReLU + 3x3 stride-2 pad-1 max pooling.
 // wf: [64][176] fp16, row k = 22 fragments of 8: fragment 3r + j holds halfs 8j..8j+7 of filter row r's 24-half window
 // {0, w[k][r][s=0][c=0..2], ..., w[k][r][6][0..2], 0, 0}; the 22nd fragment is zero.  W even.
+// w1 [64][64] fp16, b1 [64] fp32 or nullptr, t1 like y: optionally also t1 = relu(y w1^T + b1), the 1x1 convolution behind it
 int launch_stem_pool(const half_t* x, const half_t* wf, const float* bias, int N, int H, int W, half_t* y, int hp,
-                     hipStream_t stream);
+                     hipStream_t stream, const half_t* w1 = nullptr, const float* b1 = nullptr, half_t* t1 = nullptr);
 int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
                      int stride, int act, half_t* y, int hp, hipStream_t stream);
 int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream);

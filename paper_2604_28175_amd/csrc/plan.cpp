@@ -584,6 +584,8 @@ static int plan_resnet50(Model& m, Builder& b) {
             const int t1 = carry_t1 >= 0 ? carry_t1 : b.pl.get((size_t)P * Q * pln);
             carry_t1 = -1;
             if ((rc = b.conv(p + ".c1", true, cur, P, Q, cin, pln, 1, 1, 0, ACT_RELU, SLOT_NONE, t1, nullptr, nullptr))) return rc;
+            if (si == 0 && bi == 0 && m.ops[0].kind == OP_STEMPOOL && m.ops[0].out == cur && cin == 64 && pln == 64 && m.ops.back().ldw == 64)
+                m.ops[0].stem_next = (int)m.ops.size() - 1;
             const int t2 = b.pl.get((size_t)P2 * Q2 * pln);
             if ((rc = b.conv(p + ".c2", true, t1, P, Q, pln, pln, 3, stride, 1, ACT_RELU, SLOT_NONE, t2, nullptr, nullptr))) return rc;
             b.pl.put(t1);
@@ -916,6 +918,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     bool forked = false;
     hipStream_t main_stream = stream;
     int fused_away = -1;                                // op already computed by the pair launch of an earlier op
+    int stem_next_done = -1;                            // the 1x1 convolution already computed inside the fused stem
     // whether op i (a block-closing pointwise convolution) runs as one launch with the op `pair` further on, and whether
     // that launch also absorbs the block's projection shortcut; the projection op asks the same question about its block
     auto pair_here = [&](int i) {
@@ -932,7 +935,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     for (int i = first_layer; i <= last_layer; ++i) {
         const Op& op = m.ops[i];
         stream = main_stream;
-        if (i == fused_away || (op.proj_of >= 0 && pair_here(op.proj_of) >= 2)) {
+        if (i == fused_away || i == stem_next_done || (op.proj_of >= 0 && pair_here(op.proj_of) >= 2)) {
             if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
             continue;
         }
@@ -998,6 +1001,13 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 break;
             }
             case OP_STEMPOOL:
+                if (op.stem_next >= 0 && op.stem_next <= last_layer && m.ctx->pair_min_pixels > 0) {
+                    const Op& c1 = m.ops[op.stem_next];
+                    rc = launch_stem_pool((const half_t*)src, op.w, op.bias, batch, op.H, op.W, (half_t*)dst, hp, stream, c1.w, c1.bias,
+                                          (half_t*)slot_ptr(m, in, c1.out, c1.out_ref, batch));
+                    stem_next_done = op.stem_next;
+                    break;
+                }
                 rc = launch_stem_pool((const half_t*)src, op.w, op.bias, batch, op.H, op.W, (half_t*)dst, hp, stream);
                 break;
             case OP_PACK:

@@ -50,6 +50,8 @@ struct Op {
     // added), and the projection's own launch is skipped.  proj_down: on the closing convolution, the index of the
     // projection op; proj_of: on the projection op, the index of the closing convolution (-1 = none).
     int proj_down = -1, proj_of = -1;
+    // on the fused stem: the index of the 1x1 convolution (64 -> 64, ReLU) that reads nothing but its output and can run inside it
+    int stem_next = -1;
     const half_t* w_proj = nullptr;
     const float* bias_proj = nullptr;
     // implicit-GEMM addressing (elements), see ConvParams

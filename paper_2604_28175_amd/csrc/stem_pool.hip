@@ -18,6 +18,10 @@
 //   3. bias + ReLU, positions outside the convolution's output set to 0 (never above a real ReLU output,
 //      and every pooling window holds a real one), fp16 tile in LDS;
 //   4. each pooled value is the maximum of 9 LDS vectors of 8 channels.
+//   5. optionally the 1x1 convolution that follows in a residual network (64 -> 64 channels, + bias, ReLU: the first
+//      block's opening layer): the pooled tile, which the pooling pass also leaves in LDS, is the B operand of four more
+//      MFMA steps per wavefront, and the layer's own launch, with its read of the pooled tensor, goes away.  Same
+//      instruction, reduction order and rounding points as the stand-alone kernel: bit-identical.
 // With non-finite pixels the three zero-weight neighbours of a window can turn a finite result into NaN;
 // finite inputs give exactly the sum the definition gives.
 #include "kernels.hpp"
@@ -38,12 +42,15 @@ constexpr int SP_ROW_DW = 56;                             // its pitch
 constexpr int SP_LDC = 72;                                // convolution tile pitch (halfs)
 constexpr int SP_K = 64;                                  // output channels
 constexpr int SP_STEPS = 11;                              // MFMA steps of 16: 22 fragments of 8 (21 in use)
+constexpr int SP_PLD = 72;                                // pooled tile pitch (halfs)
 
 __global__ void __launch_bounds__(256, 2)
 stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, const float* __restrict__ bias, int N, int H, int W,
-                 int P, int Q, int P2, int Q2, int tiles_p, int tiles_q, half_t* __restrict__ y, int hp) {
+                 int P, int Q, int P2, int Q2, int tiles_p, int tiles_q, half_t* __restrict__ y, int hp,
+                 const half_t* __restrict__ w1, const float* __restrict__ b1, half_t* __restrict__ t1) {
     __shared__ __attribute__((aligned(16))) uint32_t patch[SP_IR * SP_ROW_DW];
     __shared__ __attribute__((aligned(16))) half_t ctile[256 * SP_LDC];
+    __shared__ __attribute__((aligned(16))) half_t ptile[64 * SP_PLD];      // pooled tile (56 pixels in use) for step 5
     if (hp) __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
 
@@ -59,6 +66,19 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
             // the prefetched patch among them, in front of every MFMA.
             asm volatile("" : "+v"(wreg[ni][t]));
         }
+
+    // step 5: this wavefront's 32 of the 64 pooled pixels (pb) and 32 of the 64 output channels (cb)
+    const int pb = wave & 1, cb = wave >> 1;
+    half8 w1f[4];
+    float b1v[4][4];
+    if (w1) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) w1f[ks] = *(const half8*)(w1 + (cb * 32 + l32) * 64 + ks * 16 + lh * 8);
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b1v[g][e] = b1 ? b1[cb * 32 + 8 * g + 4 * lh + e] : 0.f;
+    }
 
     const int total = N * tiles_p * tiles_q;          // the launcher checks that this fits
     const int row_elems = W * 3;
@@ -161,6 +181,35 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
 #pragma unroll
                 for (int k = 1; k < 9; ++k) m = __builtin_elementwise_max(m, v[k]);
                 *(half8*)(y + (((long long)n * P2 + gp) * Q2 + gq) * SP_K + c8 * 8) = m;
+                if (w1) *(half8*)(ptile + pix * SP_PLD + c8 * 8) = m;
+            } else if (w1) {
+                const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+                *(half8*)(ptile + pix * SP_PLD + c8 * 8) = z;     // outside the pooled image: multiplied, never stored
+            }
+        }
+        if (w1) {
+            __syncthreads();
+            floatx16 a1;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) a1[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const half8 pf = *(const half8*)(ptile + (pb * 32 + l32) * SP_PLD + ks * 16 + lh * 8);
+                a1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(w1f[ks], pf, a1, 0, 0, 0);
+            }
+            const int pix = pb * 32 + l32;
+            const int pp = pix / SP_TQ, pq = pix - pp * SP_TQ;
+            const int gp = P0 + pp, gq = Q0 + pq;
+            if (pix < SP_TP * SP_TQ && gp < P2 && gq < Q2) {
+                half_t* dst = t1 + (((long long)n * P2 + gp) * Q2 + gq) * SP_K + cb * 32 + 4 * lh;
+                const half4 zero4 = {(half_t)0, (half_t)0, (half_t)0, (half_t)0};
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    half4 h;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = (half_t)(a1[4 * g + e] + b1v[g][e]);
+                    *(half4*)(dst + 8 * g) = __builtin_elementwise_max(h, zero4);
+                }
             }
         }
         // The next tile's patch is written to LDS after this point: nobody reads `patch` between the barrier above and
@@ -170,15 +219,18 @@ stem_pool_kernel(const half_t* __restrict__ x, const half_t* __restrict__ wf, co
 }
 
 int launch_stem_pool(const half_t* x, const half_t* wf, const float* bias, int N, int H, int W, half_t* y, int hp,
-                     hipStream_t stream) {
+                     hipStream_t stream, const half_t* w1, const float* b1, half_t* t1) {
     if (!x || !wf || !bias || !y || N <= 0 || H < 1 || W < 2 || W % 2 != 0) { set_error("stem+pool: needs an even image width"); return -5; }
+    if ((w1 != nullptr) != (t1 != nullptr) || ((reinterpret_cast<uintptr_t>(w1) | reinterpret_cast<uintptr_t>(t1)) & 15)) {
+        set_error("stem+pool: the following 1x1 convolution needs its weights and its output, 16-byte aligned"); return -1;
+    }
     const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;          // 7x7, stride 2, pad 3
     const int P2 = (P - 1) / 2 + 1, Q2 = (Q - 1) / 2 + 1;        // 3x3, stride 2, pad 1
     const int tiles_p = (P2 + SP_TP - 1) / SP_TP, tiles_q = (Q2 + SP_TQ - 1) / SP_TQ;
     const long long total = (long long)N * tiles_p * tiles_q;
     if ((long long)H * W * 3 > 0x7fffffffLL || total > 0x7fffffffLL) { set_error("stem+pool: image or grid too large"); return -5; }
     const unsigned blocks = (unsigned)(total < 512 ? total : 512);     // 2 workgroups on each of 256 compute units
-    hipLaunchKernelGGL(stem_pool_kernel, dim3(blocks), dim3(256), 0, stream, x, wf, bias, N, H, W, P, Q, P2, Q2, tiles_p, tiles_q, y, hp);
+    hipLaunchKernelGGL(stem_pool_kernel, dim3(blocks), dim3(256), 0, stream, x, wf, bias, N, H, W, P, Q, P2, Q2, tiles_p, tiles_q, y, hp, w1, b1, t1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("stem+pool launch: %s", hipGetErrorString(e)); return -2; }
     return 0;
