@@ -284,6 +284,14 @@ strait_status strait_k_pointwise_pair_proj(void* stream, const void* x, const vo
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,
                                  int32_t hp);
+/* MobileNetV2's stem in one launch that reads the image as it lies in memory (Section 3.2 step (2): the first kernel of that
+ * network's sequence): 3x3 convolution, stride 2, pad 1, of x [N,H,W,3] to Kout channels, + bias, activation (NONE, RELU,
+ * RELU6) -> y [N,P,Q,Kout] with P = (H-1)/2+1, Q = (W-1)/2+1.  W even; Kout 8, 16, 24 or 32 (E_SHAPE otherwise).
+ * wf fp16 [32][48]: row k is three filter rows of 16 halfs, {0, w[k][r][0][c=0..2], w[k][r][1][0..2], w[k][r][2][0..2],
+ * 0, 0, 0, 0, 0, 0} (w indexed [k][r][s][c]); rows from Kout on are zero.  bias fp32 [Kout] or NULL.  Finite inputs give the
+ * sums of the definition; a non-finite pixel can reach a neighbouring window through a zero weight. */
+strait_status strait_k_stem3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
+                                 int32_t Kout, int32_t act, void* y, int32_t hp);
 /* ResNet stem in one launch: 7x7 convolution, stride 2, pad 3, of x [N,H,W,3] to 64 channels, + bias, ReLU, then 3x3
  * max pooling, stride 2, pad 1 -> y [N,P2,Q2,64] (P = (H-1)/2+1, P2 = (P-1)/2+1, likewise Q).  W even.
  * wf fp16 [64][176]: row k is 22 fragments of 8 halfs; fragment 3r + j holds halfs 8j..8j+7 of the 24-half window

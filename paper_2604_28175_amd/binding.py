@@ -92,6 +92,7 @@ _SIGS = {
     "strait_k_gemm": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_conv1x1_proj": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
+    "strait_k_stem3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_pointwise_pair": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_pointwise_pair_proj": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_dwconv3x3": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
@@ -438,6 +439,15 @@ def k_stem_pool(x, wf, bias, hp=0, stream=None):
     p, q = (h - 1) // 2 + 1, (w - 1) // 2 + 1
     y = torch.empty((n, (p - 1) // 2 + 1, (q - 1) // 2 + 1, 64), dtype=torch.float16, device=x.device)
     _check(lib.strait_k_stem_pool(_stream(stream), _dev(x), n, h, w, _dev(wf), _dev(bias), _dev(y), hp))
+    return y
+
+
+def k_stem3x3s2(x, wf, bias, kout, act=ACT_NONE, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    assert c == 3
+    y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, kout), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_stem3x3s2(_stream(stream), _dev(x), n, h, w, _dev(wf), _dev(bias), kout, act, _dev(y), hp))
     return y
 
 

@@ -707,6 +707,10 @@ strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y, int32_t hp) {
     return launch_dwconv3x3((const half_t*)x, N, H, W, C, (const half_t*)w_rsc, bias, stride, act, (half_t*)y, hp, (hipStream_t)stream);
 }
+strait_status strait_k_stem3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
+                                 int32_t Kout, int32_t act, void* y, int32_t hp) {
+    return launch_stem3x3s2((const half_t*)x, (const half_t*)wf, bias, N, H, W, Kout, act, (half_t*)y, hp, (hipStream_t)stream);
+}
 strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
     return launch_maxpool3x3s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);
 }

@@ -77,6 +77,11 @@ int launch_pack_input(const half_t* x, int N, int H, int W, int C, half_t* y, in
 // w1 [64][64] fp16, b1 [64] fp32 or nullptr, t1 like y: optionally also t1 = relu(y w1^T + b1), the 1x1 convolution behind it
 int launch_stem_pool(const half_t* x, const half_t* wf, const float* bias, int N, int H, int W, half_t* y, int hp,
                      hipStream_t stream, const half_t* w1 = nullptr, const float* b1 = nullptr, half_t* t1 = nullptr);
+// 3x3 stride-2 pad-1 convolution of a 3-channel image to Kout <= 32 channels + bias + activation (stem3x3.hip).
+// wf: [32][48] fp16, row k = 3 filter rows x 16 halfs {0, w[k][r][s=0][c=0..2], w[k][r][1][..], w[k][r][2][..], 0 x 6}; rows
+// from Kout on zero.  W even, Kout a multiple of 8.
+int launch_stem3x3s2(const half_t* x, const half_t* wf, const float* bias, int N, int H, int W, int Kout, int act, half_t* y, int hp,
+                     hipStream_t stream);
 int launch_dwconv3x3(const half_t* x, int N, int H, int W, int C, const half_t* w_rsc, const float* bias,
                      int stride, int act, half_t* y, int hp, hipStream_t stream);
 int launch_maxpool3x3s2(const half_t* x, int N, int H, int W, int C, half_t* y, int hp, hipStream_t stream);

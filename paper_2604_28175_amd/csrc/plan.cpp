@@ -230,6 +230,34 @@ struct Loader {
         op.info.weight_bytes = (int64_t)K * C * R * S * 2 + K * 4;
         return 0;
     }
+    // Direct 3x3/2 stem: OIHW [K][3][3][3] -> [32][3 filter rows][16]: a filter row's window {0, (s=0: c=0,1,2), (s=1: ..),
+    // (s=2: ..), 0 x 6}; rows from K on stay zero.
+    int stem3_weights(const std::string& name, bool bn, unsigned K, Op& op) {
+        const unsigned C = 3, R = 3, S = 3;
+        const TensorView* w = c.find(name + ".w");
+        if (!w) return STRAIT_E_FORMAT;
+        if (!shape_is(w, {K, C, R, S})) { set_error("'%s.w': expected [%u,%u,%u,%u]", name.c_str(), K, C, R, S); return STRAIT_E_FORMAT; }
+        std::vector<float> scale, bias;
+        int rc = scale_bias(name, bn, K, scale, bias);
+        if (rc) return rc;
+        const unsigned ldw = 48;
+        std::vector<half_t> out((size_t)32 * ldw, (half_t)0);
+        for (unsigned k = 0; k < K; ++k)
+            for (unsigned r = 0; r < R; ++r)
+                for (unsigned s = 0; s < S; ++s)
+                    for (unsigned cc = 0; cc < C; ++cc) {
+                        const float v = (float)w->data[((k * C + cc) * R + r) * S + s];
+                        out[(size_t)k * ldw + r * 16 + 1 + s * 3 + cc] = bn ? (half_t)(v * scale[k]) : (half_t)v;
+                    }
+        void *dw = nullptr, *db = nullptr;
+        if ((rc = upload(out.data(), out.size() * 2, &dw))) return rc;
+        if ((rc = upload(bias.data(), bias.size() * 4, &db))) return rc;
+        op.w = (const half_t*)dw;
+        op.bias = (const float*)db;
+        op.ldw = (int)ldw;
+        op.info.weight_bytes = (int64_t)K * C * R * S * 2 + K * 4;
+        return 0;
+    }
     // depthwise [C][1][3][3] -> [3][3][C]
     int dw_weights(const std::string& name, unsigned C, Op& op) {
         const TensorView* w = c.find(name + ".w");
@@ -343,6 +371,25 @@ struct Builder {
     int stem(const std::string& name, bool bn, int H, int W, int C, int K, int R, int stride, int pad, int act, int out_slot_elems_hint,
              int* out_slot, int* P_out, int* Q_out) {
         (void)out_slot_elems_hint;
+        if (C == 3 && R == 3 && stride == 2 && pad == 1 && K >= 8 && K <= 32 && K % 8 == 0 && W % 2 == 0 && act != ACT_GELU) {
+            // MobileNetV2's stem: a kernel of its own that reads the image as it lies in memory (no packed copy)
+            const int P = osz(H, 3, 2, 1), Q = osz(W, 3, 2, 1);
+            Op op;
+            name_op(op, name, 0);
+            op.kind = OP_STEM3;
+            op.in = SLOT_INPUT;
+            op.H = H; op.W = W; op.C = 3; op.K = K; op.R = op.S = 3; op.stride = 2; op.pad = 1; op.act = act;
+            op.P = P; op.Q = Q;
+            int rc = ld.stem3_weights(name, bn, (unsigned)K, op);
+            if (rc) return rc;
+            op.out = pl.get((size_t)P * Q * K);
+            op.info.macs_per_sample = (int64_t)P * Q * K * 27;
+            op.info.bytes_per_sample = 2LL * ((int64_t)H * W * 3 + (int64_t)P * Q * K);
+            op.info.gemm_m_per_sample = P * Q; op.info.gemm_n = K; op.info.gemm_k = 48;
+            m.ops.push_back(op);
+            *out_slot = op.out; *P_out = P; *Q_out = Q;
+            return 0;
+        }
         const int Cpad = (stride * 4) % 8 == 0 ? 4 : 8;
         int Sv = R;
         while ((Sv * Cpad) % 32 != 0) ++Sv;       // 32 channels per virtual tap row: the reduction then runs through the LDS-direct kernel
@@ -1009,6 +1056,9 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                     break;
                 }
                 rc = launch_stem_pool((const half_t*)src, op.w, op.bias, batch, op.H, op.W, (half_t*)dst, hp, stream);
+                break;
+            case OP_STEM3:
+                rc = launch_stem3x3s2((const half_t*)src, op.w, op.bias, batch, op.H, op.W, op.K, op.act, (half_t*)dst, hp, stream);
                 break;
             case OP_PACK:
                 rc = launch_pack_input((const half_t*)src, batch, op.H, op.W, op.C, (half_t*)dst, op.Hp, op.Wp, op.Cpad, op.pad, op.pad, hp, stream);

@@ -18,7 +18,7 @@
 
 namespace strait {
 
-enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_POOL = 2, OP_SOFTMAX = 3, OP_LAYERNORM = 4, OP_ATTENTION = 5, OP_PACK = 6, OP_TOKENS = 7, OP_STEMPOOL = 8 };
+enum OpKind { OP_CONV = 0, OP_DWCONV = 1, OP_POOL = 2, OP_SOFTMAX = 3, OP_LAYERNORM = 4, OP_ATTENTION = 5, OP_PACK = 6, OP_TOKENS = 7, OP_STEMPOOL = 8, OP_STEM3 = 9 };
 enum PoolKind { POOL_MAX3X3S2 = 0, POOL_GLOBAL_AVG = 1, POOL_ARGMAX = 2, POOL_MAX2X2S2 = 3 };
 
 // Where an operand lives.  Slots >= 0 index the instance's activation buffers; the input and
