@@ -297,6 +297,7 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const ConvParams p) {
 //   - the loads are issued from inline assembly so that the waits are ours: "all but the newest
 //     STAGES-2 slices have landed" before the barrier, rather than a wait for everything.
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uint32x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB_OFFSET = 0x80000000u;       // beyond any buffer this kernel accepts
 
@@ -932,6 +933,220 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
     }
 }
 
+// The same computation for layers whose tiles are short (one to four input slices: the eighteen tap steps of a
+// 64-channel layer take about as long as setting a tile up and putting it away).  Half as many workgroups as the
+// compute units hold at a time are launched, and each walks over every gridDim.x-th tile: the next tile's first patch
+// and first weights arrive during the last slice of the current one, in the buffers that slice no longer reads, and the
+// finished tile leaves straight from the accumulators (8 bytes per lane and store), so that no LDS is tied up and no
+// barrier separates two tiles.  All output channels in one tile (Cout == BN): weight offsets and the bias row stay put.
+// Stores count in the same in-order counter as the transfers, so they too are issued from inline assembly, every one
+// of them by every lane (a lane with nothing to store aims beyond the buffer, which drops it): the first steps of a
+// tile, whose transfers were requested before the previous tile's stores, allow exactly those stores more in flight.
+template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
+__global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_walk_kernel(const ConvParams p, const int tiles) {
+    constexpr int NW = WGM * WGN;
+    static_assert((NW == 4 || NW == 8) && BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0 && BN % (16 * NW) == 0, "unsupported tile");
+    constexpr int TM = BM / WGM, TN = BN / WGN, TMB = TM / 32, TNB = TN / 32;
+    constexpr int WI = BN / (NW * 16);
+    constexpr int PRE = NBS - 1;
+    constexpr int AS = (NPW + 8 - PRE) / (9 - PRE);
+    static_assert(NBS >= 3 && NBS <= 8, "ring depth");
+    constexpr int PATCH = NPW * NW * 1024;
+    constexpr int WSTAGE = BN * 64;
+    constexpr int RING = 2 * PATCH + NBS * WSTAGE;
+    static_assert(RING + 1024 <= 160 * 1024 && BN <= 256, "LDS limit; one transfer carries the bias row");
+
+    extern __shared__ __attribute__((aligned(1024))) half_t smem[];
+    const unsigned lds0 = (unsigned)(uintptr_t)smem;
+    if (p.hp) __builtin_amdgcn_s_setprio(3);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave % WGM) * TM, wn0 = (wave / WGM) * TN;
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    const int SW = p.strip_w, NS = __builtin_amdgcn_readfirstlane(p.W / SW);
+    const int Wp = SW + (NS == 1 ? 1 : 2), HpWp = (p.H + 1) * Wp, NI = (p.M / p.PQ) * NS;
+    const float rcp_w = 1.f / (float)Wp, rcp_i = 1.f / (float)HpWp, rcp_s = 1.f / (float)NS;
+    const intx4 xrsrc = make_rsrc(p.x, (unsigned)(p.x_elems * 2));
+    const intx4 wrsrc = make_rsrc(p.w, (unsigned)((long long)p.Cout * p.ldw * 2));
+
+    // virtual workgroup v -> tile: the hardware deals consecutive workgroups to the eight XCDs in turn, and gridDim.x is a
+    // multiple of eight, so v mod 8 is this workgroup's XCD for every v it takes; each XCD gets a contiguous range of tiles
+    auto tile_m0 = [&](int v) __attribute__((always_inline)) -> int {
+        const int per = tiles >> 3, rem = tiles & 7, xcd = v & 7, idx = v >> 3;
+        return ((xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx) * BM;
+    };
+    auto patch_offsets = [&](int m0, bool live, unsigned (&ao)[NPW]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) {
+            const int pp = (j * NW + wave) * 16 + (lane >> 2);
+            int img, rem, yp, xp, n, st;
+            divmod_f(m0 + pp, HpWp, rcp_i, img, rem);
+            divmod_f(rem, Wp, rcp_w, yp, xp);
+            divmod_f(img, NS, rcp_s, n, st);
+            const int xr = st * SW + xp - 1;
+            const int lc = (lane & 3) ^ ((pp >> 2) & 3);
+            const bool inside = live && img < NI && yp >= 1 && yp <= p.H && xr >= 0 && xr < p.W;
+            ao[j] = inside ? (unsigned)(((long long)n * p.sN + (long long)(yp - 1) * p.sH + (long long)xr * p.sW + lc * 8) * 2) : OOB_OFFSET;
+        }
+    };
+    unsigned woff[WI];
+#pragma unroll
+    for (int j = 0; j < WI; ++j) {
+        const int row = (j * NW + wave) * 16 + (lane >> 2);
+        const int lc = (lane & 3) ^ ((row >> 2) & 3);
+        woff[j] = row < p.Cout ? (unsigned)(((long long)row * p.ldw + lc * 8) * 2) : OOB_OFFSET;
+    }
+    const int ncs = p.C >> 5;
+    auto issue_w = [&](int stage, int tap, int cs, bool live) __attribute__((always_inline)) {
+        const unsigned soff = live ? (unsigned)(tap * p.C + cs * 32) * 2u : 0u;
+#pragma unroll
+        for (int j = 0; j < WI; ++j)
+            dma16(wrsrc, live ? woff[j] : OOB_OFFSET, soff, lds0 + (unsigned)(2 * PATCH + stage * WSTAGE + (j * NW + wave) * 1024));
+    };
+
+    floatx16 acc[TNB][TMB];
+#pragma unroll
+    for (int a = 0; a < TNB; ++a)
+#pragma unroll
+        for (int b = 0; b < TMB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    if (wave == 0) {                                   // the oldest transfer: every later wait covers it
+        const intx4 brsrc = make_rsrc(p.bias, p.bias ? (unsigned)p.Cout * 4u : 0u);
+        const int c = lane * 4;
+        dma16(brsrc, (p.bias && c < BN && c + 3 < p.Cout) ? (unsigned)c * 4u : OOB_OFFSET, 0u, lds0 + RING);
+    }
+    const int G = (int)gridDim.x;
+    int vb = (int)blockIdx.x;
+    int m0 = tile_m0(vb);
+    unsigned aoff[NPW], anext[NPW];
+    patch_offsets(m0, true, aoff);
+#pragma unroll
+    for (int j = 0; j < NPW; ++j) dma16(xrsrc, aoff[j], 0u, lds0 + (unsigned)((j * NW + wave) * 1024));
+#pragma unroll
+    for (int t = 0; t < PRE; ++t) issue_w(t, t, 0, true);
+    int rd = 0, wr = PRE, par = 0;
+
+    const half_t lo = (p.act == ACT_RELU || p.act == ACT_RELU6) ? (half_t)0.f : (half_t)-INFINITY;
+    const half_t hi = p.act == ACT_RELU6 ? (half_t)6.f : (half_t)INFINITY;
+    const half4 lo4 = {lo, lo, lo, lo}, hi4 = {hi, hi, hi, hi};
+    const float* bias_s = (const float*)((const char*)smem + RING);
+    const unsigned wrow = (unsigned)((lh ^ ((l32 >> 2) & 3)) << 4);
+    constexpr int NSTORE = TNB * 4 * TMB;              // stores per wave and tile
+    static_assert(patch_wait(NPW, AS, WI, PRE, 0) + NSTORE < 64, "the counter holds 63");
+    const intx4 yrsrc = make_rsrc(p.y, (unsigned)((long long)p.M * p.ldy * 2));
+
+    for (;;) {
+        const int vnext = vb + G;
+        const bool has_next = vnext < tiles;
+        const int m0n = has_next ? tile_m0(vnext) : 0;
+        patch_offsets(m0n, has_next, anext);
+        for (int cs = 0; cs < ncs; ++cs) {
+            const bool wrap = cs + 1 == ncs;           // the slice after this one is the next tile's first
+            const bool after_stores = cs == 0 && vb != (int)blockIdx.x;   // the previous tile's stores are the newest requests
+            const int csn = wrap ? 0 : cs + 1;
+            const bool nlive = !wrap || has_next;
+            unsigned asrc[NPW];
+#pragma unroll
+            for (int j = 0; j < NPW; ++j) asrc[j] = wrap ? anext[j] : aoff[j];
+            const char* Pa = (const char*)smem + par * PATCH;
+            const unsigned nbuf = lds0 + (unsigned)((par ^ 1) * PATCH);
+            int wp_l = Wp;
+            asm volatile("" : "+s"(wp_l));
+#define STRAIT_WALK_STEP(T)                                                                                             \
+            {                                                                                                           \
+                if (T < PRE && after_stores) wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T) + NSTORE>();        \
+                else wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T)>();                                         \
+                const char* Ws = (const char*)smem + 2 * PATCH + rd * WSTAGE;                                           \
+                const int tapoff = (T / 3) * wp_l + (T % 3);                                                             \
+                unsigned a0[TMB];                                                                                       \
+                _Pragma("unroll") for (int b = 0; b < TMB; ++b) {                                                       \
+                    const unsigned pp = (unsigned)(wm0 + b * 32 + l32 + tapoff);                                        \
+                    a0[b] = pp * 64u + (((lh ^ (pp >> 2)) & 3u) << 4);                                                  \
+                }                                                                                                       \
+                half8 wf[2][TNB], xf[2][TMB];                                                                           \
+                _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[0][a] = *(const half8*)(Ws + (wn0 + a * 32 + l32) * 64 + wrow); \
+                _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[0][b] = *(const half8*)(Pa + a0[b]);                 \
+                if (T + PRE < 9) issue_w(wr, T + PRE, cs, true); else issue_w(wr, T + PRE - 9, csn, nlive);             \
+                rd = rd + 1 == NBS ? 0 : rd + 1;                                                                        \
+                wr = wr + 1 == NBS ? 0 : wr + 1;                                                                        \
+                _Pragma("unroll") for (int j = T * AS; j < (T + 1) * AS && j < NPW; ++j)                                \
+                    dma16(xrsrc, asrc[j], (unsigned)csn * 64u, nbuf + (unsigned)((j * NW + wave) * 1024));             \
+                _Pragma("unroll") for (int a = 0; a < TNB; ++a) wf[1][a] = *(const half8*)(Ws + (((wn0 + a * 32 + l32) * 64 + wrow) ^ 32u)); \
+                _Pragma("unroll") for (int b = 0; b < TMB; ++b) xf[1][b] = *(const half8*)(Pa + (a0[b] ^ 32u));         \
+                __builtin_amdgcn_sched_barrier(0);                                                                      \
+                _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                        \
+                    _Pragma("unroll") for (int a = 0; a < TNB; ++a)                                                     \
+                        _Pragma("unroll") for (int b = 0; b < TMB; ++b)                                                 \
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[ks][a], xf[ks][b], acc[a][b], 0, 0, 0); \
+                __builtin_amdgcn_sched_barrier(0);                                                                      \
+            }
+            STRAIT_WALK_STEP(0) STRAIT_WALK_STEP(1) STRAIT_WALK_STEP(2) STRAIT_WALK_STEP(3) STRAIT_WALK_STEP(4)
+            STRAIT_WALK_STEP(5) STRAIT_WALK_STEP(6) STRAIT_WALK_STEP(7) STRAIT_WALK_STEP(8)
+#undef STRAIT_WALK_STEP
+            par ^= 1;
+        }
+        // ---- the tile leaves from the registers: lane (l32, lh) holds channels 8 g + 4 lh + (0..3) of pixel l32 per 32 x 32 block
+        unsigned ybase[TMB];                           // byte offset of this lane's pixel in y (the launcher keeps y below 2 GB)
+#pragma unroll
+        for (int b = 0; b < TMB; ++b) {
+            int img, rem, yy, xx, n, st;
+            divmod_f(m0 + wm0 + b * 32 + l32, HpWp, rcp_i, img, rem);
+            divmod_f(rem, Wp, rcp_w, yy, xx);
+            divmod_f(img, NS, rcp_s, n, st);
+            ybase[b] = (img < NI && yy < p.H && xx < SW) ? (unsigned)((((long long)(n * p.H + yy) * p.W + st * SW + xx) * p.ldy) * 2) : OOB_OFFSET;
+        }
+#pragma unroll
+        for (int a = 0; a < TNB; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int cn = wn0 + a * 32 + 8 * g + 4 * lh;
+                const float4 b4 = *(const float4*)(bias_s + cn);
+                const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                for (int b = 0; b < TMB; ++b) {
+                    half4 h;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { h[j] = (half_t)(acc[a][b][4 * g + j] + bv[j]); acc[a][b][4 * g + j] = 0.f; }
+                    h = __builtin_elementwise_min(__builtin_elementwise_max(h, lo4), hi4);
+                    const uint32x2 hv = __builtin_bit_cast(uint32x2, h);
+                    asm volatile("buffer_store_dwordx2 %0, %1, %2, 0 offen" ::"v"(hv), "v"(ybase[b] + (unsigned)cn * 2u), "s"(yrsrc) : "memory");
+                }
+            }
+        if (!has_next) break;
+        vb = vnext;
+        m0 = m0n;
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) aoff[j] = anext[j];
+    }
+    wait_loads_then_barrier<0>();                      // trailing (empty) transfers have landed
+}
+
+template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
+static int launch_patch_walk(const ConvParams& p, long long mv, hipStream_t stream) {
+    constexpr int NW = WGM * WGN;
+    const long long tiles = (mv + BM - 1) / BM;
+    if (p.Cout != BN || tiles < 512 || tiles > 0x7fffffffLL || (long long)p.M * p.ldy * 2 >= (1LL << 31)) {
+        set_error("conv: bad grid (%lld tiles)", tiles); return -5;
+    }
+    constexpr unsigned lds = 2 * NPW * NW * 1024 + NBS * BN * 64 + 1024;
+    static_assert(2 * (lds + 1024) <= 160 * 1024, "two workgroups per compute unit");
+    auto kernel = conv3x3_patch_walk_kernel<BM, BN, WGM, WGN, NPW, NBS>;
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire) && lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) { set_error("conv: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
+    }
+    configured.store(true, std::memory_order_release);
+    hipLaunchKernelGGL(kernel, dim3(512), dim3(64 * NW), lds, stream, p, (int)tiles);   // two workgroups on each of 256 compute units
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_error("conv launch: %s", hipGetErrorString(e)); return -2; }
+    return 0;
+}
+
 template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
 static int launch_patch_tile(const ConvParams& p, long long mv, hipStream_t stream) {
     constexpr int NW = WGM * WGN;
@@ -979,8 +1194,10 @@ static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
     }
     if (p.Cout % 64 == 0) {
         const int npw = per_wave(256, 4);
-        if (npw <= 6) return launch_patch_tile<256, 64, 4, 1, 6, 3>(p, mv, stream);
-        if (npw <= 8) return launch_patch_tile<256, 64, 4, 1, 8, 3>(p, mv, stream);
+        // 64 channels in and out and tiles enough for two per workgroup: workgroups that walk over tiles
+        const bool walk = p.Cout == 64 && p.C <= 128 && (mv + 255) / 256 >= 1024 && (long long)p.M * p.ldy * 2 < (1LL << 31);
+        if (npw <= 6) return walk ? launch_patch_walk<256, 64, 4, 1, 6, 3>(p, mv, stream) : launch_patch_tile<256, 64, 4, 1, 6, 3>(p, mv, stream);
+        if (npw <= 8) return walk ? launch_patch_walk<256, 64, 4, 1, 8, 3>(p, mv, stream) : launch_patch_tile<256, 64, 4, 1, 8, 3>(p, mv, stream);
         return -1;
     }
     return -1;

@@ -59,6 +59,10 @@ CONV_CASES = [
     (16, 112, 112, 64, 128, 3, 1, 1, 1, False, False),  # rows cut into two strips of 56; two input slices
     (48, 64, 64, 32, 128, 3, 1, 1, 0, False, False),    # 64-pixel rows: four patch transfers per wave
     (12, 128, 128, 32, 128, 3, 1, 1, 2, False, False),  # two strips of 64: four transfers per wave with real pixels on the strips' sides
+    # 64 channels out, at most 128 in and 1024 or more 256-pixel tiles: workgroups that walk over several tiles each
+    (81, 56, 56, 64, 64, 3, 1, 1, 1, False, False),     # 1028 tiles, two input slices
+    (24, 112, 112, 32, 64, 3, 1, 1, 2, False, False),   # one slice: every slice is a tile's last; rows in two strips
+    (320, 28, 28, 128, 64, 3, 1, 1, 0, False, False),   # four slices
     # few tiles and a reduction worth splitting two to eight ways: two groups of wavefronts in one workgroup, half the slices each
     (8, 14, 14, 1024, 256, 1, 1, 0, 1, False, False),   # pointwise, 64-wide slices, 16 of them
     (2, 14, 14, 512, 256, 1, 1, 0, 1, True, False),     # pointwise with residual
@@ -119,7 +123,11 @@ def test_conv2d_integer_data_is_bit_exact(S):
                                        (2, 40, 130, 32, 64),     # two strips of odd width 65
                                        (3, 21, 200, 32, 64),     # four strips of 50
                                        # the eight-wave 256 x 128 tile (768 tiles or more): three and four patch transfers per wave
-                                       (64, 56, 56, 32, 256), (16, 112, 112, 32, 128), (48, 64, 64, 32, 128), (12, 128, 128, 64, 128)])
+                                       (64, 56, 56, 32, 256), (16, 112, 112, 32, 128), (48, 64, 64, 32, 128), (12, 128, 128, 64, 128),
+                                       # workgroups that walk over tiles (64 channels out, 1024 tiles or more): two slices, one slice,
+                                       # three slices (the patch buffers swap roles from tile to tile), two strips of odd width 65
+                                       (81, 56, 56, 64, 64), (72, 60, 60, 32, 64), (300, 30, 30, 96, 64), (50, 40, 130, 32, 64),
+                                       (6, 224, 224, 64, 64)])   # and four strips of 56
 def test_conv2d_wide_3x3_integer_data_is_bit_exact(S, N, H, W, C, K):
     """The wide 3x3 stride-1 layers run from an input patch in LDS, addressed through the bordered image: with
     integer data every border, strip seam and tile seam must come out exactly."""
@@ -398,6 +406,42 @@ def test_stem_pool(S, n, h, w):
     y = S.k_stem_pool(dev(S, x), dev(S, stem_pool_weights(wt)), dev(S, b)).float().cpu().numpy()
     assert y.shape == ref.shape
     check_kernel(y, ref, f"stem+pool {n}x{h}x{w}")
+
+
+def stem3_weights(w_oihw):
+    """[K,3,3,3] -> the direct 3x3/2 stem's [32][48] layout (strait.h, strait_k_stem3x3s2)."""
+    wf = np.zeros((32, 48), np.float16)
+    k = w_oihw.shape[0]
+    for r in range(3):
+        for s in range(3):
+            for c in range(3):
+                wf[:k, r * 16 + 1 + s * 3 + c] = w_oihw[:, c, r, s]
+    return wf
+
+
+@pytest.mark.parametrize("n,h,w,k,act", [(2, 64, 64, 32, 2), (1, 224, 224, 32, 2), (3, 51, 38, 32, 1), (2, 7, 8, 16, 0), (1, 33, 66, 24, 2),
+                                         (2, 1, 2, 8, 0), (1, 130, 226, 32, 2), (5, 18, 130, 32, 2), (40, 96, 96, 32, 2)])
+def test_stem3x3s2(S, n, h, w, k, act):
+    x = f16(R.standard_normal((n, h, w, 3)))
+    wt = f16(R.standard_normal((k, 3, 3, 3)) * (2.0 / 27) ** 0.5)
+    b = (R.standard_normal(k) * 0.5).astype(np.float32)
+    ref = act_ref(ops.conv2d(x, wt, b, 2, 1), act)
+    y = S.k_stem3x3s2(dev(S, x), dev(S, stem3_weights(wt)), dev(S, b), k, act=act).float().cpu().numpy()
+    assert y.shape == ref.shape
+    check_kernel(y, ref, f"stem 3x3/2 {n}x{h}x{w}->{k}")
+
+
+def test_stem3x3s2_integer_data_and_errors(S):
+    # small integers: every product and partial sum is exact in fp16 and fp32, so any order of summation gives the same bits
+    x = R.integers(-3, 4, (3, 45, 70, 3)).astype(np.float16)
+    wt = R.integers(-2, 3, (32, 3, 3, 3)).astype(np.float16)
+    b = R.integers(-4, 5, 32).astype(np.float32)
+    y = S.k_stem3x3s2(dev(S, x), dev(S, stem3_weights(wt)), dev(S, b), 32, act=2).float().cpu().numpy()
+    assert np.array_equal(y, ops.relu6(ops.conv2d(x, wt, b, 2, 1)))
+    with pytest.raises(S.StraitError):       # odd width
+        S.k_stem3x3s2(dev(S, x[:, :, :69]), dev(S, stem3_weights(wt)), dev(S, b), 32)
+    with pytest.raises(S.StraitError):       # a channel count the kernel does not take
+        S.k_stem3x3s2(dev(S, x), dev(S, stem3_weights(wt)), dev(S, b), 12)
 
 
 @pytest.mark.parametrize("n,h,w,c", [(2, 8, 6, 16), (3, 14, 14, 512), (1, 224, 224, 64)])
