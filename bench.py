@@ -403,7 +403,7 @@ def main() -> int:
                      "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": measured_traffic(B),
                      "traffic_source": TRAFFIC_FILE + " (rocprofv3 FETCH_SIZE and WRITE_SIZE runs of this command, committed; null when a kernel source has changed since)",
                      "algorithmic_bytes_per_step": sum(float(layers[i].bytes_per_sample) * B + layers[i].weight_bytes for i in conv),
-                     "kernel": "conv_igemm_dma_kernel (all tile shapes), conv3x3_patch_kernel, pointwise_pair_wave_kernel and stem_pool_kernel: the MFMA launches of a step (53 convolutions and the classifier, in fewer launches than layers: the stem with the pooling and the first 1x1 convolution behind it, every projection shortcut inside its block's closing convolution, three block seams of the first stage as pairs)",
+                     "kernel": "conv_igemm_dma_kernel (all tile shapes), conv3x3_patch_kernel and its tile-walking form, pointwise_pair_wave_kernel and stem_pool_kernel: the MFMA launches of a step (53 convolutions and the classifier, in fewer launches than layers: the stem with the pooling and the first 1x1 convolution behind it, every projection shortcut inside its block's closing convolution, three block seams of the first stage as pairs)",
                      "flops_per_step": conv_flops, "kernel_ms_per_step": round(conv_ms, 4),
                      "other_kernels_ms_per_step": round(other_ms, 4),
                      "layerwise_roofline_ms": round(t_roof * 1e3, 4),
