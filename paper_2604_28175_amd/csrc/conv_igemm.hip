@@ -297,7 +297,6 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const ConvParams p) {
 //   - the loads are issued from inline assembly so that the waits are ours: "all but the newest
 //     STAGES-2 slices have landed" before the barrier, rather than a wait for everything.
 typedef int intx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uint32x2 __attribute__((ext_vector_type(2)));
 
 constexpr unsigned OOB_OFFSET = 0x80000000u;       // beyond any buffer this kernel accepts
 
@@ -939,9 +938,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_k
 // and first weights arrive during the last slice of the current one, in the buffers that slice no longer reads, and the
 // finished tile leaves straight from the accumulators (8 bytes per lane and store), so that no LDS is tied up and no
 // barrier separates two tiles.  All output channels in one tile (Cout == BN): weight offsets and the bias row stay put.
-// Stores count in the same in-order counter as the transfers, so they too are issued from inline assembly, every one
-// of them by every lane (a lane with nothing to store aims beyond the buffer, which drops it): the first steps of a
-// tile, whose transfers were requested before the previous tile's stores, allow exactly those stores more in flight.
+// Stores count in the same counter as the transfers.  The waits of the tap steps are not adjusted for them: a wait
+// that allows the n newest requests in flight then also waits for stores issued before those, which costs the first
+// steps of a tile a little time (counting them in was worth 1 us in 50) and never lets a transfer be read early.
 template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
 __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_walk_kernel(const ConvParams p, const int tiles) {
     constexpr int NW = WGM * WGN;
@@ -1035,9 +1034,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_w
     const half4 lo4 = {lo, lo, lo, lo}, hi4 = {hi, hi, hi, hi};
     const float* bias_s = (const float*)((const char*)smem + RING);
     const unsigned wrow = (unsigned)((lh ^ ((l32 >> 2) & 3)) << 4);
-    constexpr int NSTORE = TNB * 4 * TMB;              // stores per wave and tile
-    static_assert(patch_wait(NPW, AS, WI, PRE, 0) + NSTORE < 64, "the counter holds 63");
-    const intx4 yrsrc = make_rsrc(p.y, (unsigned)((long long)p.M * p.ldy * 2));
 
     for (;;) {
         const int vnext = vb + G;
@@ -1046,7 +1042,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_w
         patch_offsets(m0n, has_next, anext);
         for (int cs = 0; cs < ncs; ++cs) {
             const bool wrap = cs + 1 == ncs;           // the slice after this one is the next tile's first
-            const bool after_stores = cs == 0 && vb != (int)blockIdx.x;   // the previous tile's stores are the newest requests
             const int csn = wrap ? 0 : cs + 1;
             const bool nlive = !wrap || has_next;
             unsigned asrc[NPW];
@@ -1058,8 +1053,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_w
             asm volatile("" : "+s"(wp_l));
 #define STRAIT_WALK_STEP(T)                                                                                             \
             {                                                                                                           \
-                if (T < PRE && after_stores) wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T) + NSTORE>();        \
-                else wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T)>();                                         \
+                wait_loads_then_barrier<patch_wait(NPW, AS, WI, PRE, T)>();                                              \
                 const char* Ws = (const char*)smem + 2 * PATCH + rd * WSTAGE;                                           \
                 const int tapoff = (T / 3) * wp_l + (T % 3);                                                             \
                 unsigned a0[TMB];                                                                                       \
@@ -1090,14 +1084,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_w
             par ^= 1;
         }
         // ---- the tile leaves from the registers: lane (l32, lh) holds channels 8 g + 4 lh + (0..3) of pixel l32 per 32 x 32 block
-        unsigned ybase[TMB];                           // byte offset of this lane's pixel in y (the launcher keeps y below 2 GB)
+        long long ybase[TMB];                          // this lane's pixel in y, in elements; -1: a border slot, nothing to store
 #pragma unroll
         for (int b = 0; b < TMB; ++b) {
             int img, rem, yy, xx, n, st;
             divmod_f(m0 + wm0 + b * 32 + l32, HpWp, rcp_i, img, rem);
             divmod_f(rem, Wp, rcp_w, yy, xx);
             divmod_f(img, NS, rcp_s, n, st);
-            ybase[b] = (img < NI && yy < p.H && xx < SW) ? (unsigned)((((long long)(n * p.H + yy) * p.W + st * SW + xx) * p.ldy) * 2) : OOB_OFFSET;
+            ybase[b] = (img < NI && yy < p.H && xx < SW) ? ((long long)(n * p.H + yy) * p.W + st * SW + xx) * p.ldy : -1;
         }
 #pragma unroll
         for (int a = 0; a < TNB; ++a)
@@ -1112,8 +1106,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, WGM * WGN / 2) conv3x3_patch_w
 #pragma unroll
                     for (int j = 0; j < 4; ++j) { h[j] = (half_t)(acc[a][b][4 * g + j] + bv[j]); acc[a][b][4 * g + j] = 0.f; }
                     h = __builtin_elementwise_min(__builtin_elementwise_max(h, lo4), hi4);
-                    const uint32x2 hv = __builtin_bit_cast(uint32x2, h);
-                    asm volatile("buffer_store_dwordx2 %0, %1, %2, 0 offen" ::"v"(hv), "v"(ybase[b] + (unsigned)cn * 2u), "s"(yrsrc) : "memory");
+                    if (ybase[b] >= 0) *(half4*)((half_t*)p.y + ybase[b] + cn) = h;
                 }
             }
         if (!has_next) break;
@@ -1129,9 +1122,7 @@ template <int BM, int BN, int WGM, int WGN, int NPW, int NBS>
 static int launch_patch_walk(const ConvParams& p, long long mv, hipStream_t stream) {
     constexpr int NW = WGM * WGN;
     const long long tiles = (mv + BM - 1) / BM;
-    if (p.Cout != BN || tiles < 512 || tiles > 0x7fffffffLL || (long long)p.M * p.ldy * 2 >= (1LL << 31)) {
-        set_error("conv: bad grid (%lld tiles)", tiles); return -5;
-    }
+    if (p.Cout != BN || tiles < 512 || tiles > 0x7fffffffLL) { set_error("conv: bad grid (%lld tiles)", tiles); return -5; }
     constexpr unsigned lds = 2 * NPW * NW * 1024 + NBS * BN * 64 + 1024;
     static_assert(2 * (lds + 1024) <= 160 * 1024, "two workgroups per compute unit");
     auto kernel = conv3x3_patch_walk_kernel<BM, BN, WGM, WGN, NPW, NBS>;
@@ -1195,7 +1186,7 @@ static int launch_conv3x3_patch(const ConvParams& params, hipStream_t stream) {
     if (p.Cout % 64 == 0) {
         const int npw = per_wave(256, 4);
         // 64 channels in and out and tiles enough for two per workgroup: workgroups that walk over tiles
-        const bool walk = p.Cout == 64 && p.C <= 128 && (mv + 255) / 256 >= 1024 && (long long)p.M * p.ldy * 2 < (1LL << 31);
+        const bool walk = p.Cout == 64 && p.C <= 128 && (mv + 255) / 256 >= 1024;
         if (npw <= 6) return walk ? launch_patch_walk<256, 64, 4, 1, 6, 3>(p, mv, stream) : launch_patch_tile<256, 64, 4, 1, 6, 3>(p, mv, stream);
         if (npw <= 8) return walk ? launch_patch_walk<256, 64, 4, 1, 8, 3>(p, mv, stream) : launch_patch_tile<256, 64, 4, 1, 8, 3>(p, mv, stream);
         return -1;
