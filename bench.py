@@ -310,7 +310,11 @@ def main() -> int:
             kinds = {1: "depthwise_conv3x3", 2: "pooling", 3: "softmax", 4: "layernorm"}
             hk = {}
             for i, l in enumerate(olayers):
-                if l.kind in kinds and l.bytes_per_sample > 0:
+                if l.kind in kinds and l.bytes_per_sample > 0 and lms[i] == 0.0:
+                    # computed inside another layer's launch at this batch size (run_timed gives exactly 0): not a launch
+                    hk.setdefault(kinds[l.kind], {"launches": 0, "bytes": 0.0, "ms": 0.0, "best_gbs": 0.0}).setdefault("fused_into_other_launches", 0)
+                    hk[kinds[l.kind]]["fused_into_other_launches"] += 1
+                elif l.kind in kinds and l.bytes_per_sample > 0:
                     e = hk.setdefault(kinds[l.kind], {"launches": 0, "bytes": 0.0, "ms": 0.0, "best_gbs": 0.0})
                     by = float(l.bytes_per_sample) * 64 + l.weight_bytes
                     e["launches"] += 1

@@ -217,7 +217,8 @@ strait_status strait_run(strait_model* m, int32_t instance, strait_priority prio
 strait_status strait_copy_out(strait_model* m, int32_t instance, strait_priority prio, int32_t batch, void* host_out);
 strait_status strait_sync(strait_model* m, int32_t instance, strait_priority prio);
 /* Like strait_run, with a hipEvent pair around every layer; after an internal synchronise,
- * layer_ms[i] (host, float[n_layers]) holds layer i's device time. */
+ * layer_ms[i] (host, float[n_layers]) holds layer i's device time: exactly 0 for a layer that was computed inside
+ * another layer's launch at this batch size (its time is in that layer's figure). */
 strait_status strait_run_timed(strait_model* m, int32_t instance, strait_priority prio, int32_t batch,
                                float* layer_ms);
 /* Copies an intermediate activation (the output of layer `layer`) of the instance's last run
@@ -284,6 +285,15 @@ strait_status strait_k_pointwise_pair_proj(void* stream, const void* x, const vo
 strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C,
                                  const void* w_rsc, const float* bias, int32_t stride, int32_t act, void* y,
                                  int32_t hp);
+/* The first two layers of an inverted residual block in one launch (Section 3.2 step (2): two members of MobileNetV2's
+ * kernel sequence): a 1x1 convolution x [N,H,W,Cin] -> Chid channels, + b1, act1, and the depthwise 3x3 convolution of
+ * stride 1 or 2 and padding 1 behind it, + bd, act2 -> y [N,P,Q,Chid] with P = (H-1)/stride+1, Q = (W-1)/stride+1.  The
+ * expanded tensor exists only tile by tile in LDS.  w1 fp16 [Chid][Cin], wd_rsc fp16 [3][3][Chid], b1 and bd fp32 [Chid] or
+ * NULL; activations NONE, RELU or RELU6.  Cin a multiple of 8 up to 160, Chid a multiple of 8 (E_SHAPE otherwise); all
+ * pointers 16-byte aligned (E_INVALID).  Results are bit-identical to strait_k_conv2d followed by strait_k_dwconv3x3. */
+strait_status strait_k_expand_dw(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t Cin, const void* w1,
+                                 const float* b1, int32_t Chid, int32_t act1, const void* wd_rsc, const float* bd, int32_t stride,
+                                 int32_t act2, void* y, int32_t hp);
 /* MobileNetV2's stem in one launch that reads the image as it lies in memory (Section 3.2 step (2): the first kernel of that
  * network's sequence): 3x3 convolution, stride 2, pad 1, of x [N,H,W,3] to Kout channels, + bias, activation (NONE, RELU,
  * RELU6) -> y [N,P,Q,Kout] with P = (H-1)/2+1, Q = (W-1)/2+1.  W even; Kout 8, 16, 24 or 32 (E_SHAPE otherwise).

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstrait.so")
-SOURCES = ["conv_igemm.hip", "elementwise.hip", "attention.hip", "stem_pool.hip", "noalloc.hip", "pointwise_pair.hip", "stem3x3.hip", "plan.cpp", "api.cpp", "link.cpp", "intf.cpp", "sched.cpp", "server.cpp"]
+SOURCES = ["conv_igemm.hip", "elementwise.hip", "attention.hip", "stem_pool.hip", "noalloc.hip", "pointwise_pair.hip", "stem3x3.hip", "expand_dw.hip", "plan.cpp", "api.cpp", "link.cpp", "intf.cpp", "sched.cpp", "server.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-result",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mf16c"]

@@ -577,7 +577,10 @@ strait_status strait_run_timed(strait_model* m, int32_t instance, strait_priorit
     rc = run_plan(*m, in, batch, s, hp_flag(m->ctx, prio), -1, true);
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(s));
-    for (size_t i = 0; i < m->ops.size(); ++i) HIP_TRY(hipEventElapsedTime(&layer_ms[i], in.layer_ev[i], in.layer_ev[i + 1]));
+    for (size_t i = 0; i < m->ops.size(); ++i) {
+        HIP_TRY(hipEventElapsedTime(&layer_ms[i], in.layer_ev[i], in.layer_ev[i + 1]));
+        if (in.layer_skipped[i]) layer_ms[i] = 0.f;    // its time is in the launch that computed it (between its events: nothing)
+    }
     return STRAIT_OK;
 }
 
@@ -710,6 +713,12 @@ strait_status strait_k_dwconv3x3(void* stream, const void* x, int32_t N, int32_t
 strait_status strait_k_stem3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
                                  int32_t Kout, int32_t act, void* y, int32_t hp) {
     return launch_stem3x3s2((const half_t*)x, (const half_t*)wf, bias, N, H, W, Kout, act, (half_t*)y, hp, (hipStream_t)stream);
+}
+strait_status strait_k_expand_dw(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t Cin, const void* w1,
+                                 const float* b1, int32_t Chid, int32_t act1, const void* wd_rsc, const float* bd, int32_t stride,
+                                 int32_t act2, void* y, int32_t hp) {
+    return launch_expand_dw((const half_t*)x, N, H, W, Cin, (const half_t*)w1, Cin, b1, Chid, act1, (const half_t*)wd_rsc, bd, stride, act2,
+                            (half_t*)y, hp, (hipStream_t)stream);
 }
 strait_status strait_k_maxpool3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t C, void* y, int32_t hp) {
     return launch_maxpool3x3s2((const half_t*)x, N, H, W, C, (half_t*)y, hp, (hipStream_t)stream);

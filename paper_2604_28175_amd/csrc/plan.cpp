@@ -696,6 +696,7 @@ static int plan_mobilenet_v2(Model& m, Builder& b) {
             const int d = b.pl.get((size_t)P2 * Q2 * hid);
             int Pd, Qd;
             if ((rc = b.dwconv(p + ".dw", a, P, Q, hid, stride, d, &Pd, &Qd))) return rc;
+            if (t != 1 && expand_dw_supported(cin, hid, stride)) m.ops[m.ops.size() - 2].dw_next = true;
             if (a != cur) b.pl.put(a);
             const bool residual = stride == 1 && cin == cout;
             const int o = b.pl.get((size_t)P2 * Q2 * cout);
@@ -964,6 +965,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
     const bool branches = !timed && first_layer == 0 && last_layer == n - 1 && in.side != nullptr && m.ctx->branch_streams;
     bool forked = false;
     hipStream_t main_stream = stream;
+    if (timed) in.layer_skipped.assign(m.ops.size(), 0);
     int fused_away = -1;                                // op already computed by the pair launch of an earlier op
     int stem_next_done = -1;                            // the 1x1 convolution already computed inside the fused stem
     // whether op i (a block-closing pointwise convolution) runs as one launch with the op `pair` further on, and whether
@@ -983,7 +985,7 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
         const Op& op = m.ops[i];
         stream = main_stream;
         if (i == fused_away || i == stem_next_done || (op.proj_of >= 0 && pair_here(op.proj_of) >= 2)) {
-            if (timed) HIP_TRY(hipEventRecord(in.layer_ev[i], stream));
+            if (timed) { HIP_TRY(hipEventRecord(in.layer_ev[i], stream)); in.layer_skipped[i] = 1; }
             continue;
         }
         // a branch pays a fork and a join (two event hand-overs between streams): only worth it for a launch
@@ -1005,6 +1007,19 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
         int rc = 0;
         switch (op.kind) {
             case OP_CONV: {
+                // An inverted residual block's expansion and depthwise layer as one launch, the expanded tensor staying in
+                // LDS.  It pays where launches are what a batch costs (MobileNetV2 up to batch 8: -3.5 to -7 % per batch) and
+                // on the one layer whose expanded tensor dwarfs its input and output while two workgroups still fit a compute
+                // unit (112 x 112 x 16 -> 96 at stride 2: -10 % per batch of 64 or 128); elsewhere the two launches, each
+                // with every lane busy, are as fast or faster (all blocks fused at batch 64: +3 %).
+                if (op.dw_next && i + 1 <= last_layer && m.ctx->pair_min_pixels > 0 &&
+                    (batch <= 8 || (m.ops[i + 1].stride == 2 && op.vC <= 16 && (long long)batch * op.P * op.Q * op.K >= 36000000LL))) {
+                    const Op& dw = m.ops[i + 1];
+                    rc = launch_expand_dw((const half_t*)src, batch, op.P, op.Q, op.vC, op.w, op.ldw, op.bias, op.K, op.act, dw.w, dw.bias,
+                                          dw.stride, dw.act, (half_t*)slot_ptr(m, in, dw.out, dw.out_ref, batch), hp, stream);
+                    fused_away = i + 1;
+                    break;
+                }
                 const int how = pair_here(i);
                 if (how == 1 || how == 2) {
                     const Op& nx = m.ops[i + op.pair];

@@ -52,6 +52,8 @@ struct Op {
     int proj_down = -1, proj_of = -1;
     // on the fused stem: the index of the 1x1 convolution (64 -> 64, ReLU) that reads nothing but its output and can run inside it
     int stem_next = -1;
+    // on a 1x1 expansion: the next op is the depthwise 3x3 that alone reads its output, and both can run as one launch
+    bool dw_next = false;
     const half_t* w_proj = nullptr;
     const float* bias_proj = nullptr;
     // implicit-GEMM addressing (elements), see ConvParams
@@ -84,6 +86,7 @@ struct Instance {
     hipStream_t side = nullptr;        // default priority, non-blocking: carries branches that do not depend on each other
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::vector<hipEvent_t> layer_ev;
+    std::vector<char> layer_skipped;    // by the last timed run: layers that were computed inside another layer's launch
     // Captured kernel sequences, keyed by (batch, wave-priority flag); a key is captured on its second
     // use, after one eager pass has set the kernels' attributes outside of any capture.
     std::map<std::pair<int, int>, hipGraphExec_t> graphs;

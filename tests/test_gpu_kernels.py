@@ -444,6 +444,50 @@ def test_stem3x3s2_integer_data_and_errors(S):
         S.k_stem3x3s2(dev(S, x), dev(S, stem3_weights(wt)), dev(S, b), 12)
 
 
+EXPAND_DW_CASES = [
+    # N, H, W, Cin, Chid, stride      (MobileNetV2's blocks at their real shapes, then ragged ones)
+    (2, 112, 112, 16, 96, 2), (2, 56, 56, 24, 144, 1), (2, 56, 56, 24, 144, 2), (3, 28, 28, 32, 192, 1), (3, 28, 28, 32, 192, 2),
+    (4, 14, 14, 64, 384, 1), (4, 14, 14, 96, 576, 1), (4, 14, 14, 96, 576, 2), (5, 7, 7, 160, 960, 1),
+    (2, 15, 13, 40, 88, 1),       # 40 input channels in a 64-wide reduction, 88 = 2 groups of 32 and 24 channels, odd image
+    (1, 9, 10, 8, 8, 2),          # one group with 8 channels, the smallest of everything
+    (2, 37, 45, 48, 200, 2),      # stride 2 with ragged tiles in both directions, a ragged last group
+    (70, 14, 14, 64, 384, 1),     # enough tiles that a workgroup takes all twelve groups
+    (1, 20, 70, 160, 64, 2),      # 160 input channels at stride 2: only the smallest tile fits LDS
+]
+
+
+@pytest.mark.parametrize("case", EXPAND_DW_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_expand_dw(S, case):
+    """1x1 expansion + depthwise 3x3 as one launch: against the oracle's two operators, and bit for bit against the two
+    stand-alone kernels."""
+    N, H, W, Cin, Chid, stride = case
+    x = f16(R.standard_normal((N, H, W, Cin)))
+    w1 = f16(R.standard_normal((Chid, Cin, 1, 1)) * (2.0 / Cin) ** 0.5)
+    b1 = R.standard_normal(Chid).astype(np.float32)
+    wd = f16(R.standard_normal((Chid, 1, 3, 3)) * 0.47)
+    bd = R.standard_normal(Chid).astype(np.float32)
+    hid = ops.relu6(ops.conv2d(x, w1, b1, 1, 0))
+    ref = ops.relu6(ops.dwconv2d(hid, wd, bd, stride, 1))
+    w1_d = dev(S, np.ascontiguousarray(w1[:, :, 0, 0]))
+    wd_d = dev(S, np.ascontiguousarray(np.transpose(wd[:, 0], (1, 2, 0))))
+    y = S.k_expand_dw(dev(S, x), w1_d, dev(S, b1), wd_d, dev(S, bd), stride)
+    t = S.k_conv2d(dev(S, x), w1_d.reshape(Chid, 1, 1, Cin), dev(S, b1), 1, 0, 2)
+    y2 = S.k_dwconv3x3(t, wd_d, dev(S, bd), stride, 2)
+    S.torch.cuda.synchronize()
+    assert tuple(y.shape) == ref.shape
+    assert S.torch.equal(y, y2), f"fused differs from the two launches {case}"
+    check_kernel(y.float().cpu().numpy(), ref, f"expand+dw {case}")
+
+
+def test_expand_dw_errors(S):
+    x = dev(S, np.zeros((1, 8, 8, 12), np.float16))
+    with pytest.raises(S.StraitError):       # Cin % 8 != 0
+        S.k_expand_dw(x, dev(S, np.zeros((16, 12), np.float16)), None, dev(S, np.zeros((3, 3, 16), np.float16)), None, 1)
+    x = dev(S, np.zeros((1, 8, 8, 16), np.float16))
+    with pytest.raises(S.StraitError):       # stride 3
+        S.k_expand_dw(x, dev(S, np.zeros((16, 16), np.float16)), None, dev(S, np.zeros((3, 3, 16), np.float16)), None, 3)
+
+
 @pytest.mark.parametrize("n,h,w,c", [(2, 8, 6, 16), (3, 14, 14, 512), (1, 224, 224, 64)])
 def test_maxpool2x2(S, n, h, w, c):
     x = f16(R.standard_normal((n, h, w, c)))

@@ -129,6 +129,44 @@ def test_mobilenet_v2(ctx, hw, batch):
     m.free()
 
 
+def test_mobilenet_v2_fused_expansions_equal_separate_launches(ctx):
+    """Up to batch 8 every inverted residual block runs its expansion and its depthwise layer as one launch (and the
+    112 x 112 one at any batch large enough); the kernel takes the same arithmetic steps, so the whole network's output
+    must be bit-identical with the fusion switched off, and the oracle's within tolerance."""
+    md = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2])
+    x = synth.default_image_batch(md, 6, 99)
+    m = ctx.load(synth.pack(md), max_batch=6, n_instances=1)
+    try:
+        ctx.set_pair_fusion(0)
+        sep, _ = m.infer(x, prio=ctx.S.PRIO_LOW)
+        ctx.set_pair_fusion(40000)
+        fused, _ = m.infer(x, prio=ctx.S.PRIO_LOW)
+        assert np.array_equal(sep["logits"], fused["logits"]) and np.array_equal(sep["top1"], fused["top1"])
+        ref = omodels.mobilenet_v2_forward(md.tensors, x)
+        check_logits(fused["logits"], ref.logits, fused["top1"], "MobileNetV2 b6, fused expansions")
+    finally:
+        ctx.set_pair_fusion(40000)
+        m.free()
+
+
+def test_run_timed_gives_zero_for_layers_inside_another_launch(ctx):
+    """Per-layer times: a layer that runs inside its predecessor's launch reads exactly 0, every launch a positive time."""
+    md = synth.mobilenet_v2(synth.SEEDS[synth.ARCH_MOBILENETV2], hw=64)
+    m = ctx.load(synth.pack(md), max_batch=4, n_instances=1)
+    try:
+        m.copy_in(0, ctx.S.PRIO_LOW, synth.default_image_batch(md, 4, 3))
+        names = [l.name.decode() for l in m.layers()]
+        ms = m.run_timed(0, ctx.S.PRIO_LOW, 4)
+        inside = [n for n, t in zip(names, ms) if t == 0.0]
+        assert inside == [f"b{i}.dw" for i in range(1, 17)], inside          # every block with an expansion; b0 has none
+        assert all(t > 0.0 for n, t in zip(names, ms) if n not in inside)
+        ctx.set_pair_fusion(0)
+        assert all(t > 0.0 for t in m.run_timed(0, ctx.S.PRIO_LOW, 4))
+    finally:
+        ctx.set_pair_fusion(40000)
+        m.free()
+
+
 @pytest.mark.parametrize("kw,batch", [(dict(layers=2, hidden=128, heads=2, ffn=256, seq=64), 3),
                                       (dict(layers=2, hidden=128, heads=2, ffn=256, seq=48), 3),      # no multiple of the 32-row blocks
                                       (dict(layers=1, hidden=64, heads=1, ffn=128, seq=200), 2),      # more than 128 keys
