@@ -275,11 +275,17 @@ static int launch_edw_ks(const ExpandDwParams& p, int stride, hipStream_t stream
         return launch_edw_tile<KS, 1, 8, 1>(p, stream);
     }
     // stride 2 puts four input pixels under an output: with many input channels only the smallest tile fits LDS
-    if constexpr (edw_lds_bytes(KS, 2, 32, 2) <= 160 * 1024) {
+    // (two workgroups per compute unit matter more than a tile's ratio of rim to area: half the height where the taller tile
+    // would take more than half of LDS)
+    if constexpr (edw_lds_bytes(KS, 2, 32, 2) <= 80 * 1024) {
         if (p.Q > 16) return launch_edw_tile<KS, 2, 32, 2>(p, stream);
+    } else if constexpr (edw_lds_bytes(KS, 2, 32, 1) <= 160 * 1024) {
+        if (p.Q > 16) return launch_edw_tile<KS, 2, 32, 1>(p, stream);
     }
-    if constexpr (edw_lds_bytes(KS, 2, 16, 2) <= 160 * 1024) {
+    if constexpr (edw_lds_bytes(KS, 2, 16, 2) <= 80 * 1024) {
         if (p.Q > 8) return launch_edw_tile<KS, 2, 16, 2>(p, stream);
+    } else if constexpr (edw_lds_bytes(KS, 2, 16, 1) <= 160 * 1024) {
+        if (p.Q > 8) return launch_edw_tile<KS, 2, 16, 1>(p, stream);
     }
     return launch_edw_tile<KS, 2, 8, 1>(p, stream);
 }
