@@ -302,6 +302,12 @@ strait_status strait_k_expand_dw(void* stream, const void* x, int32_t N, int32_t
  * sums of the definition; a non-finite pixel can reach a neighbouring window through a zero weight. */
 strait_status strait_k_stem3x3s2(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
                                  int32_t Kout, int32_t act, void* y, int32_t hp);
+/* The same stem with 32 output channels and the stride-1 depthwise 3x3 convolution of MobileNetV2's first block behind it
+ * (padding 1, wd_rsc fp16 [3][3][32], + bd fp32 [32] or NULL, act2) in one launch: y [N,P,Q,32]; the stem's output stays in
+ * LDS.  wf, bias, act1 as for strait_k_stem3x3s2.  W even (E_SHAPE otherwise), pointers 16-byte aligned.  Results are
+ * bit-identical to strait_k_stem3x3s2 followed by strait_k_dwconv3x3. */
+strait_status strait_k_stem3x3s2_dw(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
+                                    int32_t act1, const void* wd_rsc, const float* bd, int32_t act2, void* y, int32_t hp);
 /* ResNet stem in one launch: 7x7 convolution, stride 2, pad 3, of x [N,H,W,3] to 64 channels, + bias, ReLU, then 3x3
  * max pooling, stride 2, pad 1 -> y [N,P2,Q2,64] (P = (H-1)/2+1, P2 = (P-1)/2+1, likewise Q).  W even.
  * wf fp16 [64][176]: row k is 22 fragments of 8 halfs; fragment 3r + j holds halfs 8j..8j+7 of the 24-half window

@@ -93,6 +93,7 @@ _SIGS = {
     "strait_k_gemm_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32]),
     "strait_k_conv1x1_proj": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_expand_dw": (_i32, [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
+    "strait_k_stem3x3s2_dw": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _i32]),
     "strait_k_stem3x3s2": (_i32, [_vp, _vp, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i32]),
     "strait_k_pointwise_pair": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
     "strait_k_pointwise_pair_proj": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32]),
@@ -440,6 +441,15 @@ def k_stem_pool(x, wf, bias, hp=0, stream=None):
     p, q = (h - 1) // 2 + 1, (w - 1) // 2 + 1
     y = torch.empty((n, (p - 1) // 2 + 1, (q - 1) // 2 + 1, 64), dtype=torch.float16, device=x.device)
     _check(lib.strait_k_stem_pool(_stream(stream), _dev(x), n, h, w, _dev(wf), _dev(bias), _dev(y), hp))
+    return y
+
+
+def k_stem3x3s2_dw(x, wf, bias, wd_rsc, bd, act1=ACT_RELU6, act2=ACT_RELU6, hp=0, stream=None):
+    import torch
+    n, h, w, c = x.shape
+    assert c == 3
+    y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, 32), dtype=torch.float16, device=x.device)
+    _check(lib.strait_k_stem3x3s2_dw(_stream(stream), _dev(x), n, h, w, _dev(wf), _dev(bias), act1, _dev(wd_rsc), _dev(bd), act2, _dev(y), hp))
     return y
 
 

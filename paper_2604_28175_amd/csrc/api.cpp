@@ -714,6 +714,11 @@ strait_status strait_k_stem3x3s2(void* stream, const void* x, int32_t N, int32_t
                                  int32_t Kout, int32_t act, void* y, int32_t hp) {
     return launch_stem3x3s2((const half_t*)x, (const half_t*)wf, bias, N, H, W, Kout, act, (half_t*)y, hp, (hipStream_t)stream);
 }
+strait_status strait_k_stem3x3s2_dw(void* stream, const void* x, int32_t N, int32_t H, int32_t W, const void* wf, const float* bias,
+                                    int32_t act1, const void* wd_rsc, const float* bd, int32_t act2, void* y, int32_t hp) {
+    return launch_stem3x3s2_dw((const half_t*)x, (const half_t*)wf, bias, act1, (const half_t*)wd_rsc, bd, act2, N, H, W, (half_t*)y, hp,
+                               (hipStream_t)stream);
+}
 strait_status strait_k_expand_dw(void* stream, const void* x, int32_t N, int32_t H, int32_t W, int32_t Cin, const void* w1,
                                  const float* b1, int32_t Chid, int32_t act1, const void* wd_rsc, const float* bd, int32_t stride,
                                  int32_t act2, void* y, int32_t hp) {

@@ -82,6 +82,10 @@ int launch_stem_pool(const half_t* x, const half_t* wf, const float* bias, int N
 // from Kout on zero.  W even, Kout a multiple of 8.
 int launch_stem3x3s2(const half_t* x, const half_t* wf, const float* bias, int N, int H, int W, int Kout, int act, half_t* y, int hp,
                      hipStream_t stream);
+// The same stem (32 output channels) with a stride-1 depthwise 3x3 behind it (wd_rsc [3][3][32], + bd, act2) in one launch;
+// y [N,P,Q,32].  Bit-identical to launch_stem3x3s2 followed by launch_dwconv3x3.
+int launch_stem3x3s2_dw(const half_t* x, const half_t* wf, const float* bias, int act1, const half_t* wd_rsc, const float* bd, int act2,
+                        int N, int H, int W, half_t* y, int hp, hipStream_t stream);
 // 1x1 convolution Cin -> Chid (+ b1, act1) and the depthwise 3x3 of stride 1 or 2, padding 1, behind it (+ bd, act2) in one
 // launch (expand_dw.hip): x [N,H,W,Cin] -> y [N,P,Q,Chid]; w1 [Chid][ldw1], wd_rsc [3][3][Chid].  Bit-identical to the two
 // launches.  expand_dw_supported: whether the kernel takes these channel counts and this stride.

@@ -697,6 +697,9 @@ static int plan_mobilenet_v2(Model& m, Builder& b) {
             int Pd, Qd;
             if ((rc = b.dwconv(p + ".dw", a, P, Q, hid, stride, d, &Pd, &Qd))) return rc;
             if (t != 1 && expand_dw_supported(cin, hid, stride)) m.ops[m.ops.size() - 2].dw_next = true;
+            // the first block has no expansion: its depthwise layer reads the stem's output, and the two can be one launch
+            if (t == 1 && idx == 0 && stride == 1 && hid == 32 && m.ops.size() >= 2 && m.ops[m.ops.size() - 2].kind == OP_STEM3)
+                m.ops[m.ops.size() - 2].dw_next = true;
             if (a != cur) b.pl.put(a);
             const bool residual = stride == 1 && cin == cout;
             const int o = b.pl.get((size_t)P2 * Q2 * cout);
@@ -1073,6 +1076,14 @@ int run_plan(Model& m, Instance& in, int batch, hipStream_t stream, int hp, int 
                 rc = launch_stem_pool((const half_t*)src, op.w, op.bias, batch, op.H, op.W, (half_t*)dst, hp, stream);
                 break;
             case OP_STEM3:
+                if (op.dw_next && i + 1 <= last_layer && m.ctx->pair_min_pixels > 0) {
+                    // with the first block's depthwise layer behind it in the same launch: the stem's output stays in LDS
+                    const Op& dw = m.ops[i + 1];
+                    rc = launch_stem3x3s2_dw((const half_t*)src, op.w, op.bias, op.act, dw.w, dw.bias, dw.act, batch, op.H, op.W,
+                                             (half_t*)slot_ptr(m, in, dw.out, dw.out_ref, batch), hp, stream);
+                    fused_away = i + 1;
+                    break;
+                }
                 rc = launch_stem3x3s2((const half_t*)src, op.w, op.bias, batch, op.H, op.W, op.K, op.act, (half_t*)dst, hp, stream);
                 break;
             case OP_PACK:

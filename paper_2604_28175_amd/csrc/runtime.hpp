@@ -52,7 +52,7 @@ struct Op {
     int proj_down = -1, proj_of = -1;
     // on the fused stem: the index of the 1x1 convolution (64 -> 64, ReLU) that reads nothing but its output and can run inside it
     int stem_next = -1;
-    // on a 1x1 expansion: the next op is the depthwise 3x3 that alone reads its output, and both can run as one launch
+    // on a 1x1 expansion or the 3x3/2 stem: the next op is the depthwise 3x3 that alone reads its output, and both can run as one launch
     bool dw_next = false;
     const half_t* w_proj = nullptr;
     const float* bias_proj = nullptr;

@@ -444,6 +444,27 @@ def test_stem3x3s2_integer_data_and_errors(S):
         S.k_stem3x3s2(dev(S, x), dev(S, stem3_weights(wt)), dev(S, b), 12)
 
 
+@pytest.mark.parametrize("n,h,w", [(2, 64, 64), (1, 224, 224), (3, 51, 38), (2, 7, 8), (2, 1, 2), (1, 130, 226), (5, 18, 122), (40, 96, 96)])
+def test_stem3x3s2_dw(S, n, h, w):
+    """Stem 3x3/2 (3 -> 32) + depthwise 3x3 as one launch: against the oracle's two operators, and bit for bit against the
+    two stand-alone kernels."""
+    x = f16(R.standard_normal((n, h, w, 3)))
+    wt = f16(R.standard_normal((32, 3, 3, 3)) * (2.0 / 27) ** 0.5)
+    b = (R.standard_normal(32) * 0.5).astype(np.float32)
+    wd = f16(R.standard_normal((32, 1, 3, 3)) * 0.47)
+    bd = R.standard_normal(32).astype(np.float32)
+    ref = ops.relu6(ops.dwconv2d(ops.relu6(ops.conv2d(x, wt, b, 2, 1)), wd, bd, 1, 1))
+    wf_d, wd_d = dev(S, stem3_weights(wt)), dev(S, np.ascontiguousarray(np.transpose(wd[:, 0], (1, 2, 0))))
+    y = S.k_stem3x3s2_dw(dev(S, x), wf_d, dev(S, b), wd_d, dev(S, bd))
+    y2 = S.k_dwconv3x3(S.k_stem3x3s2(dev(S, x), wf_d, dev(S, b), 32, act=2), wd_d, dev(S, bd), 1, 2)
+    S.torch.cuda.synchronize()
+    assert tuple(y.shape) == ref.shape
+    assert S.torch.equal(y, y2), f"fused differs from the two launches {n}x{h}x{w}"
+    check_kernel(y.float().cpu().numpy(), ref, f"stem + dw {n}x{h}x{w}")
+    with pytest.raises(S.StraitError):       # odd width
+        S.k_stem3x3s2_dw(dev(S, x[:, :, :w - 1]), wf_d, dev(S, b), wd_d, dev(S, bd))
+
+
 EXPAND_DW_CASES = [
     # N, H, W, Cin, Chid, stride      (MobileNetV2's blocks at their real shapes, then ragged ones)
     (2, 112, 112, 16, 96, 2), (2, 56, 56, 24, 144, 1), (2, 56, 56, 24, 144, 2), (3, 28, 28, 32, 192, 1), (3, 28, 28, 32, 192, 2),
