@@ -58,16 +58,16 @@ __global__ void __launch_bounds__(256) expand_dw_kernel(const ExpandDwParams p) 
     if (p.hp) __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lh = lane >> 5;
 
-    int tile;
-    {   // every XCD takes a contiguous range of tiles: neighbouring tiles share rim pixels through one L2
-        const unsigned nb = gridDim.x, b = blockIdx.x;
-        const unsigned per = nb >> 3, rem = nb & 7, xcd = b & 7, idx = b >> 3;
-        tile = (int)((xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx);
-    }
-    const int tq = tile % p.tiles_q, rest = tile / p.tiles_q;
-    const int tp = rest % p.tiles_p, n = rest / p.tiles_p;
-    const int P0 = tp * TP, Q0 = tq * TQ;
-    const int ih0 = P0 * STRIDE - 1, iw0 = Q0 * STRIDE - 1;
+    // A workgroup takes every gridDim.x-th tile.  Virtual workgroup v -> tile: every XCD takes a contiguous range of tiles
+    // (neighbouring tiles share rim pixels through one L2); v mod 8 is this workgroup's XCD for every v it takes, because
+    // a grid smaller than the number of tiles is a multiple of eight.
+    const int ntiles = p.N * p.tiles_p * p.tiles_q;
+    auto tile_of = [&](int v, int& n, int& P0, int& Q0) __attribute__((always_inline)) {
+        const unsigned per = (unsigned)ntiles >> 3, rem = (unsigned)ntiles & 7, xcd = (unsigned)v & 7, idx = (unsigned)v >> 3;
+        const int tile = (int)((xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx);
+        const int tq = tile % p.tiles_q, rest = tile / p.tiles_q;
+        Q0 = tq * TQ; P0 = (rest % p.tiles_p) * TP; n = rest / p.tiles_p;
+    };
     const int groups = (p.Chid + 31) >> 5;
     const int g_begin = (int)blockIdx.y * p.groups_per_block;
     const int g_end = g_begin + p.groups_per_block < groups ? g_begin + p.groups_per_block : groups;
@@ -112,46 +112,60 @@ __global__ void __launch_bounds__(256) expand_dw_kernel(const ExpandDwParams p) 
     load_w1(g_begin, wf, bv);
     load_wd(g_begin, wv, bdv);
 
-    // ---- A: the input tile --------------------------------------------------------------------------------------
-    // Up to eight 16-byte pieces per thread are requested before the first of them is waited for (every request from an
-    // address inside the image, the pieces outside it replaced by zeros afterwards): one round trip to memory per eight.
-    {
-        constexpr int CH = KS * 2;                                             // 16-byte pieces per pixel, zero-padded
-        constexpr int TOTAL = ROWS * CH, NIT = (TOTAL + 255) / 256, BATCH = 8;
+    // ---- A: the input tile: its 16-byte pieces are requested into registers (every request from an address inside the
+    // image, several before the first is waited for) and deposited in LDS, zeros where the piece lies outside the image.
+    // Where a thread holds few enough of them, the next tile's are requested while this tile is computed.
+    constexpr int CH = KS * 2;                                                 // 16-byte pieces per pixel, zero-padded
+    constexpr int TOTAL = ROWS * CH, NIT = (TOTAL + 255) / 256;
+    constexpr bool AHEAD = NIT <= 12;
+    constexpr int BATCH = AHEAD ? NIT : 8;
+    half8 xv[BATCH];
+    bool xok[BATCH];
+    auto request_tile = [&](int v, int it0) __attribute__((always_inline)) {
+        int n, P0, Q0;
+        tile_of(v, n, P0, Q0);
+        const int ih0 = P0 * STRIDE - 1, iw0 = Q0 * STRIDE - 1;
         const half_t* img = p.x + (long long)n * p.H * p.W * p.Cin;
 #pragma unroll
-        for (int it0 = 0; it0 < NIT; it0 += BATCH) {
-            half8 v[BATCH];
-            bool ok[BATCH];
-#pragma unroll
-            for (int b = 0; b < BATCH; ++b) {
-                if (it0 + b >= NIT) break;
-                const int id = tid + (it0 + b) * 256;
-                const int px = id / CH, ch = id - px * CH;
-                const int ir = px / IC, ic = px - ir * IC;
-                const int ih = ih0 + ir, iw = iw0 + ic;
-                ok[b] = px < NPX && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W && ch * 8 < p.Cin;
-                const long long off = ok[b] ? ((long long)ih * p.W + iw) * p.Cin + ch * 8 : 0;
-                v[b] = *(const half8*)(img + off);
-            }
-#pragma unroll
-            for (int b = 0; b < BATCH; ++b) {
-                if (it0 + b >= NIT) break;
-                const int id = tid + (it0 + b) * 256;
-                const int px = id / CH, ch = id - px * CH;
-                half8 z;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) z[j] = ok[b] ? v[b][j] : (half_t)0.f;
-                if (id < TOTAL) *(half8*)(xs + px * XP + ch * 8) = z;
-            }
+        for (int b = 0; b < BATCH; ++b) {
+            const int id = tid + (it0 + b) * 256;
+            const int px = id / CH, ch = id - px * CH;
+            const int ir = px / IC, ic = px - ir * IC;
+            const int ih = ih0 + ir, iw = iw0 + ic;
+            xok[b] = id < TOTAL && px < NPX && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W && ch * 8 < p.Cin;
+            const long long off = xok[b] ? ((long long)ih * p.W + iw) * p.Cin + ch * 8 : 0;
+            xv[b] = *(const half8*)(img + off);
         }
-    }
+    };
+    auto deposit_tile = [&](int it0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+            const int id = tid + (it0 + b) * 256;
+            const int px = id / CH, ch = id - px * CH;
+            half8 z;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) z[j] = xok[b] ? xv[b][j] : (half_t)0.f;
+            if (id < TOTAL) *(half8*)(xs + px * XP + ch * 8) = z;
+        }
+    };
     const half_t lo1 = (p.act1 == ACT_RELU || p.act1 == ACT_RELU6) ? (half_t)0.f : (half_t)-INFINITY;
     const half_t hi1 = p.act1 == ACT_RELU6 ? (half_t)6.f : (half_t)INFINITY;
     const half4 lo4 = {lo1, lo1, lo1, lo1}, hi4 = {hi1, hi1, hi1, hi1};
     const half4 zero4 = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
 
+    if (AHEAD) request_tile((int)blockIdx.x, 0);
+    for (int v = (int)blockIdx.x; v < ntiles; v += (int)gridDim.x) {
+    int n, P0, Q0;
+    tile_of(v, n, P0, Q0);
+    const int ih0 = P0 * STRIDE - 1, iw0 = Q0 * STRIDE - 1;
+    if (AHEAD) {
+        deposit_tile(0);
+    } else {
+#pragma unroll
+        for (int it0 = 0; it0 < NIT; it0 += BATCH) { request_tile(v, it0); deposit_tile(it0); }
+    }
     __syncthreads();                                                           // the input tile is in place
+    if (AHEAD && v + (int)gridDim.x < ntiles) request_tile(v + (int)gridDim.x, 0);
 
     for (int g = g_begin; g < g_end; ++g) {
         const int cd = 32 * g + 8 * c8;
@@ -178,8 +192,9 @@ __global__ void __launch_bounds__(256) expand_dw_kernel(const ExpandDwParams p) 
                 *(half4*)(hs + px * EDW_HP + 8 * g4 + 4 * lh) = inside ? h : zero4;
             }
         }
-        load_w1(g + 1, wf_next, bv_next);                                     // for the next group, while this one goes on
-        load_wd(g + 1, wv_next, bdv_next);
+        const int g_next = g + 1 < g_end ? g + 1 : g_begin;                   // after a tile's last group: the next tile's first
+        load_w1(g_next, wf_next, bv_next);                                    // requested while this group goes on
+        load_wd(g_next, wv_next, bdv_next);
         lds_barrier();
         // ---- B2: depthwise 3x3 from the expanded tile --------------------------------------------------------------
         {
@@ -230,6 +245,7 @@ __global__ void __launch_bounds__(256) expand_dw_kernel(const ExpandDwParams p) 
             for (int e = 0; e < 4; ++e) bv[g4][e] = bv_next[g4][e];
         lds_barrier();                                                         // the next group overwrites the expanded tile
     }
+    }
 }
 
 constexpr unsigned edw_lds_bytes(int ks, int stride, int tq, int th) {
@@ -260,7 +276,10 @@ static int launch_edw_tile(const ExpandDwParams& q, hipStream_t stream) {
         if (e != hipSuccess) { set_error("expand+depthwise: cannot reserve %u bytes of LDS: %s", lds, hipGetErrorString(e)); return -2; }
     }
     configured.store(true, std::memory_order_release);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)tiles, gy), dim3(256), lds, stream, p);
+    // where the kernel requests a tile's input one tile ahead, two workgroups per compute unit walk over the tiles
+    constexpr int IRr = (TP - 1) * STRIDE + 3, ICc = (TQ - 1) * STRIDE + 3, NITs = (((IRr * ICc + 31) / 32 * 32) * KS * 2 + 255) / 256;
+    const unsigned gx = (NITs <= 12 && tiles > 512) ? 512u : (unsigned)tiles;
+    hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3(256), lds, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_error("expand+depthwise launch: %s", hipGetErrorString(e)); return -2; }
     return 0;
