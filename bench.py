@@ -18,7 +18,8 @@ input already sits in device memory.  Prints ONE JSON line:
                 images/s, ms per step, TFLOP/s, and the fraction of the layer-wise roofline (sum over the layers of
                 max(flops / MFMA peak, bytes / HBM peak)) at that batch size
   hbm_kernels   the bandwidth-bound kernels (depthwise convolution, pooling, softmax in MobileNetV2 b64; LayerNorm in the
-                encoder b64): algorithmic bytes / per-layer event time, as GB/s and as a fraction of the HBM peak
+                encoder b64): algorithmic bytes / per-layer event time, as GB/s and as a fraction of the HBM peak;
+                depthwise_conv3x3_kernel_alone: that kernel through its C-ABI hook on the three largest depthwise layers
   two_instances images/s when the same K steps are issued alternately to two instances of the model on
                 the two compute streams (the paper's servers run several instances at once); not `value`
 """
@@ -328,6 +329,36 @@ def main() -> int:
                 e["best_layer_frac_of_hbm_peak"] = round(e["best_layer_gbs"] / HBM_PEAK_GBS, 4)
                 e["ms"] = round(e["ms"], 4)
                 e["bytes"] = int(e["bytes"])
+            if arch == synth.ARCH_MOBILENETV2:
+                # The depthwise kernel by itself on the network's three largest depthwise layers (two of which the plan runs
+                # inside other launches at this batch size): the C ABI's kernel hook on seeded random tensors, three sets of
+                # buffers in rotation (0.3 to 0.6 GB: more than the 256 MB memory-side cache holds), stream events around 24 launches.
+                alone = {}
+                for name, hh, cc, st in (("b0.dw 112x112x32 s1", 112, 32, 1), ("b1.dw 112x112x96 s2", 112, 96, 2), ("b2.dw 56x56x144 s1", 56, 144, 1)):
+                    g = torch.Generator(device="cuda").manual_seed(1234)
+                    xs = [torch.randn((64, hh, hh, cc), generator=g, device="cuda", dtype=torch.float16) for _ in range(3)]
+                    wd = torch.randn((3, 3, cc), generator=g, device="cuda", dtype=torch.float16) * 0.4
+                    bd = torch.randn((cc,), generator=g, device="cuda", dtype=torch.float32)
+                    pq = (hh - 1) // st + 1
+                    ys = [torch.empty((64, pq, pq, cc), device="cuda", dtype=torch.float16) for _ in range(3)]
+                    sp = torch.cuda.current_stream().cuda_stream
+
+                    def dw(i):
+                        strait.binding._check(strait.lib.strait_k_dwconv3x3(sp, xs[i % 3].data_ptr(), 64, hh, hh, cc, wd.data_ptr(), bd.data_ptr(),
+                                                                           st, 2, ys[i % 3].data_ptr(), 0))
+                    for i in range(6):
+                        dw(i)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(24):
+                        dw(i)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) / 24 * 1e3
+                    by = 2.0 * 64 * cc * (hh * hh + pq * pq)
+                    alone[name] = {"us": round(us, 2), "gbs": round(by / us / 1e3, 1), "frac_of_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
+                    del xs, ys
+                hk["depthwise_conv3x3_kernel_alone"] = alone
             res["hbm_kernels"] = hk
         om.free()
         return res
